@@ -1,0 +1,146 @@
+"""CPU oracle for the DS-Sync hot path -- TEST INFRASTRUCTURE ONLY.
+
+Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
+``bench.py`` may import this package.  It shares nothing with the GPU library:
+the arithmetic lives in ``ds_oracle.c`` (plain C, fp64) and in ``mixing.py``
+(dense mixing matrices, numpy fp64), and this file only marshals numpy arrays
+into the C routines.
+
+Paper passages implemented (see ``ds_oracle.c`` for the details):
+Listing 1 (local optimizer step, then ``Average(model, group)``), Sec. III-A
+step 4, Sec. IV-B2 (``X_{k+1} = W_k X_k``; Lemma 1's left-hand side).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ds_oracle.c")
+_LIB = os.path.join(_HERE, "libds_oracle.so")
+
+
+def build(force: bool = False) -> str:
+    """Compile ds_oracle.c with gcc (fp contraction off, OpenMP on)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        i32p = ctypes.POINTER(ctypes.c_int32)
+        lib.orc_mix64.restype = ctypes.c_uint64
+        lib.orc_mix64.argtypes = [ctypes.c_uint64]
+        lib.orc_key.restype = ctypes.c_uint64
+        lib.orc_key.argtypes = [ctypes.c_uint64, ctypes.c_uint64]
+        lib.orc_partition.restype = ctypes.c_int
+        lib.orc_partition.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int32, i32p,
+                                      ctypes.c_int32, i32p, i32p]
+        lib.orc_step.restype = ctypes.c_int
+        lib.orc_step.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int64,
+                                 ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32,
+                                 i32p, i32p, ctypes.c_int32, ctypes.c_float]
+        lib.orc_consensus.restype = ctypes.c_int
+        lib.orc_consensus.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
+                                      ctypes.c_int32, ctypes.c_void_p]
+        lib.orc_num_threads.restype = ctypes.c_int
+        lib.orc_num_threads.argtypes = []
+        _lib = lib
+    return _lib
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a, dtype=np.int32))
+
+
+def _ptr(a: np.ndarray, ctype=ctypes.c_int32):
+    return a.ctypes.data_as(ctypes.POINTER(ctype))
+
+
+def mix64(z: int) -> int:
+    """splitmix64 finaliser."""
+    return int(_load().orc_mix64(ctypes.c_uint64(z & (2**64 - 1))))
+
+
+def key(seed: int, t: int) -> int:
+    """Per-iteration shuffle key; a pure function of (seed, t)."""
+    return int(_load().orc_key(ctypes.c_uint64(seed & (2**64 - 1)), ctypes.c_uint64(t & (2**64 - 1))))
+
+
+def partition(seed: int, t: int, W: int, sizes: Sequence[int]) -> Tuple[np.ndarray, np.ndarray]:
+    """Division of workers 0..W-1 into groups for iteration ``t``.
+
+    Returns ``(perm[W], off[n_groups+1])``; group k is ``perm[off[k]:off[k+1]]``.
+    """
+    sz = _i32(sizes)
+    perm = np.empty(max(W, 1), dtype=np.int32)
+    off = np.empty(len(sz) + 1, dtype=np.int32)
+    rc = _load().orc_partition(ctypes.c_uint64(seed), ctypes.c_uint64(t), W, _ptr(sz), len(sz),
+                               _ptr(perm), _ptr(off))
+    if rc != 0:
+        raise ValueError("sizes %r do not divide %d workers" % (list(sizes), W))
+    return perm[:W], off
+
+
+def step(X: np.ndarray, G: np.ndarray, perm, off, lr: float,
+         col0: int = 0, ncols: int | None = None) -> None:
+    """One DS-Sync step in place on ``X`` (fp32 ``[W, ldx]``, C-contiguous).
+
+    ``G`` is fp32 ``[W, ldg]`` or bf16 given as raw ``uint16`` bit patterns.
+    Only columns ``col0 .. col0+ncols-1`` are touched.
+    """
+    if X.dtype != np.float32 or X.ndim != 2 or not X.flags.c_contiguous:
+        raise TypeError("X must be a C-contiguous fp32 [W, ld] array")
+    if G.ndim != 2 or not G.flags.c_contiguous or G.shape[0] != X.shape[0]:
+        raise TypeError("G must be a C-contiguous [W, ld] array")
+    if G.dtype == np.float32:
+        is_bf16 = 0
+    elif G.dtype == np.uint16:
+        is_bf16 = 1
+    else:
+        raise TypeError("G must be float32 or uint16 (bf16 bits)")
+    W, ldx = X.shape
+    ldg = G.shape[1]
+    if ncols is None:
+        ncols = min(ldx, ldg) - col0
+    if col0 < 0 or ncols < 0 or col0 + ncols > min(ldx, ldg):
+        raise ValueError("column range outside the arrays")
+    perm = _i32(perm)
+    off = _i32(off)
+    if sorted(perm.tolist()) != list(range(W)) or off[0] != 0 or off[-1] != W or np.any(np.diff(off) < 1):
+        raise ValueError("not a division of the workers into non-empty groups")
+    rc = _load().orc_step(X.ctypes.data, G.ctypes.data, is_bf16, col0, ncols, ldx, ldg, W,
+                          _ptr(perm), _ptr(off), len(off) - 1, ctypes.c_float(lr))
+    if rc != 0:
+        raise MemoryError("orc_step failed")
+
+
+def consensus(X: np.ndarray, P: int | None = None) -> np.ndarray:
+    """``d_i = || X[i,:P] - mean_j X[j,:P] ||_2`` for every worker i, fp64."""
+    if X.dtype != np.float32 or X.ndim != 2 or not X.flags.c_contiguous:
+        raise TypeError("X must be a C-contiguous fp32 [W, ld] array")
+    W, ld = X.shape
+    if P is None:
+        P = ld
+    out = np.empty(W, dtype=np.float64)
+    rc = _load().orc_consensus(X.ctypes.data, P, ld, W, out.ctypes.data)
+    if rc != 0:
+        raise MemoryError("orc_consensus failed")
+    return out
+
+
+def num_threads() -> int:
+    return int(_load().orc_num_threads())
