@@ -1,0 +1,172 @@
+#!/usr/bin/env python3
+"""Benchmark of the DS-Sync hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input, all
+resident in HBM before the clock starts:
+    ds_partition (host)  ->  ds_group_sync (GPU)  ->  ds_consensus (GPU)
+The workload is configuration 3 of the benchmark set: W = 32 workers in groups
+of 8, P = 25,557,032 fp32 parameters per replica (ResNet-50-sized), gradients
+g_i = c_i (mu + 0.5 z_i), seed 2, lr 0.01, a new division every step.
+
+Prints ONE JSON line.  ``value`` is the algorithmic bytes of a step
+(16 B per worker-element: read x, read g, write x, read x again for the
+consensus pass) divided by the wall-clock step time.  ``roofline`` is for the
+dominant kernel, the fused group-sync (12 B per worker-element), timed with
+events on the stream it is launched on.  ``cpu_baseline`` is the CPU oracle on
+the host cores, a reported figure only.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published
+
+
+def measured_traffic(name: str):
+    """HBM bytes per launch derived from rocprofv3 counter runs, if a summary
+    has been recorded under profiles/ (see the design doc); otherwise None."""
+    path = os.path.join(ROOT, "profiles", name)
+    try:
+        with open(path) as fh:
+            return json.load(fh).get("hbm_bytes_per_launch")
+    except (OSError, ValueError):
+        return None
+
+
+def cpu_baseline(cfg, X, G, iters: int):
+    """The oracle, as it stands, on the host cores: whole configuration-3 stacks."""
+    import numpy as np
+    import oracle
+    Xh = X.cpu().numpy()
+    Gh = G.cpu().numpy()
+    W, P = Xh.shape
+    t_step = t_cons = 0.0
+    for t in range(iters):
+        a = time.perf_counter()
+        perm, off = oracle.partition(cfg.seed, 1000 + t, W, cfg.sizes)
+        oracle.step(Xh, Gh, perm, off, cfg.lr)
+        b = time.perf_counter()
+        oracle.consensus(Xh)
+        c = time.perf_counter()
+        t_step += b - a
+        t_cons += c - b
+    total = t_step + t_cons
+    return {
+        "value": round(16.0 * W * P * iters / total / 1e9, 3),
+        "unit": "GB/s",
+        "cores": oracle.num_threads(),
+        "kind": "oracle",
+        "sample": "all %d columns x %d workers of the same workload, %d iterations "
+                  "(partition + step + consensus), %.1f s wall" % (P, W, iters, total),
+        "ms_per_step": round(total / iters * 1e3, 2),
+        "group_sync_ms": round(t_step / iters * 1e3, 2),
+        "consensus_ms": round(t_cons / iters * 1e3, 2),
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=3, help="benchmark configuration (flat fp32 ones: 1-4)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (W simulated workers stacked in one HBM); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2007_03298_amd as ds
+    from paper_2007_03298_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    dev = "cuda:0"
+    cfg = wl.CONFIGS[args.config]
+    if cfg.ragged:
+        print("bench.py: --config must be one of the flat configurations 1-4", file=sys.stderr)
+        return 2
+    W, P = cfg.W, cfg.P
+    run = wl.Run(cfg, dev)
+    X = run.init_params()
+    n_grad = 2                                   # gradient stacks resident in HBM, used in turn
+    Gs = [run.gradients() for _ in range(n_grad)]
+    ws_bytes = ds.ds_consensus_workspace_bytes(W, P)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    dev_out = torch.zeros(W, dtype=torch.float64, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step(t, ev=None):
+        perm, off = ds.ds_partition(cfg.seed, t, W, cfg.sizes)
+        if ev:
+            ev[0].record(stream)
+        ds.ds_group_sync(X, Gs[t % n_grad], ds.DS_F32, P, P, P, W, perm, off, cfg.lr, stream)
+        if ev:
+            ev[1].record(stream)
+        ds.ds_consensus(X, P, P, W, dev_out, ws, ws_bytes, stream)
+        if ev:
+            ev[2].record(stream)
+
+    for t in range(args.warmup):
+        step(t)
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(args.warmup + k, events[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    ms_step = (t1 - t0) / args.steps * 1e3
+    sync_ms = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps
+    cons_ms = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
+    sync_bytes = 12.0 * W * P
+    cons_bytes = 4.0 * W * P
+    sync_gbps = sync_bytes / (sync_ms * 1e-3) / 1e9
+    cons_gbps = cons_bytes / (cons_ms * 1e-3) / 1e9
+    value = (sync_bytes + cons_bytes) / (ms_step * 1e-3) / 1e9
+    d = dev_out.cpu()
+
+    out = {
+        "metric": "DS-Sync step (partition + fused group-sync + consensus) algorithmic HBM GB/s",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "W": W, "group_size": cfg.group, "P": P, "lr": cfg.lr,
+                   "seed": cfg.seed, "bytes_per_step": int(sync_bytes + cons_bytes)},
+        "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
+        "group_sync": {"ms": round(sync_ms, 4), "GBps": round(sync_gbps, 1),
+                       "pct_of_hbm_peak": round(100.0 * sync_gbps / HBM_PEAK_GBPS, 2)},
+        "consensus": {"ms": round(cons_ms, 4), "GBps": round(cons_gbps, 1),
+                      "pct_of_hbm_peak": round(100.0 * cons_gbps / HBM_PEAK_GBPS, 2),
+                      "max_deviation": float(d.max())},
+        "roofline": {"bound": "hbm", "kernel": "group_sync_kernel<float, flat>", "achieved": round(sync_gbps, 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(sync_gbps / HBM_PEAK_GBPS, 4),
+                     "traffic": measured_traffic("group_sync_cfg%d_traffic.json" % args.config)},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, X, Gs[0], iters=3)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

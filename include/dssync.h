@@ -1,0 +1,182 @@
+/*
+ * dssync.h -- C ABI of the MI355X (gfx950) DS-Sync hot path.
+ *
+ * One DS-Sync synchronisation step over W simulated worker replicas that are
+ * stacked, one row per worker, in one GPU's HBM:
+ *
+ *   1. ds_partition        divide the workers into non-overlapping groups for
+ *                          iteration t                       (host, integer)
+ *   2. ds_group_sync       every worker applies its local SGD update, then the
+ *      ds_group_sync_ragged  updated parameters are averaged inside each group
+ *                          and the mean is written back to every member (GPU)
+ *   3. ds_consensus        distance of every replica from the mean replica (GPU)
+ *
+ * Conventions shared by every entry point
+ *   - Return value: DS_OK (0) or a negative ds_status.  Nothing throws or aborts.
+ *   - All argument checks run on the host BEFORE the first HIP call, so every
+ *     error other than DS_ERR_HIP is reported without touching a GPU, and a
+ *     call that returns an error has enqueued nothing.
+ *   - "dev" pointers are device memory on the current HIP device, "host"
+ *     pointers ordinary host memory.  Every buffer is owned by the caller.
+ *     Host arrays are consumed before the call returns.  Device buffers must
+ *     stay valid until `stream` has executed the enqueued work.
+ *   - GPU work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream).  No entry point synchronises, allocates or frees
+ *     device memory, except ds_ragged_plan (a one-off set-up call, see there).
+ *   - The library keeps no state between calls.
+ *   - Row-major stacks: element (worker i, column p) of a stack with leading
+ *     dimension ld is at base + i*ld + p, ld >= P.  Replica stacks are fp32.
+ */
+#ifndef DSSYNC_H
+#define DSSYNC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DS_OK            =  0,
+    DS_ERR_NULL      = -1,  /* a required pointer is NULL                                  */
+    DS_ERR_BAD_W     = -2,  /* W outside 1..DS_MAX_W                                       */
+    DS_ERR_BAD_SIZES = -3,  /* group sizes: n_groups < 1, a size < 1, or sum != W          */
+    DS_ERR_BAD_PART  = -4,  /* perm is not a permutation of 0..W-1, or off is not 0..W
+                               strictly increasing                                         */
+    DS_ERR_BAD_SHAPE = -5,  /* P < 0, ld < P, bad segment table, size overflow             */
+    DS_ERR_ALIGN     = -6,  /* base pointer, leading dimension or segment offset breaks
+                               the alignment rule stated at the entry point                */
+    DS_ERR_DTYPE     = -7,  /* g_dtype is neither DS_F32 nor DS_BF16                       */
+    DS_ERR_WORKSPACE = -8,  /* workspace / plan buffer NULL, misaligned or too small       */
+    DS_ERR_HIP       = -9   /* a HIP call or kernel launch failed                          */
+} ds_status;
+
+/* gradient element type */
+enum { DS_F32 = 0, DS_BF16 = 1 };
+
+/* Largest number of workers.  The division of the workers travels inside the
+   kernel-argument block, so no host-to-device copy sits on the path. */
+#define DS_MAX_W 64
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char* ds_status_string(int status);
+
+/*
+ * ds_partition -- the group of every worker in iteration t.
+ *
+ * Paper: Listing 1 ("pick the proper group to synchronize for worker i in the
+ * iteration t") and Sec. IV-B2 (each iteration's groups are disjoint and cover
+ * all workers; groups may differ in size, Sec. III-A).  The paper's list is
+ * derived from the network topology; this routine draws iteration t's entry
+ * with a counter-based shuffle instead, so any (seed, t) can be evaluated in
+ * any order and nothing is carried between iterations:
+ *     gamma = 0x9E3779B97F4A7C15, mix = splitmix64 finaliser
+ *     s = mix(mix(seed) + (t+1)*gamma);  each draw: s += gamma, r = mix(s)
+ *     perm = identity; for i = W-1 .. 1: j = floor(r*(i+1) / 2^64), swap perm[i], perm[j]
+ * Group k is perm_out[off_out[k] .. off_out[k+1]-1] with off_out the prefix
+ * sums of sizes.
+ *
+ *   seed, t     shuffle key and iteration number
+ *   W           number of workers, 1..DS_MAX_W
+ *   sizes       host [n_groups], each >= 1, summing to W
+ *   perm_out    host [W], written
+ *   off_out     host [n_groups+1], written
+ * Host only: integer arithmetic, no GPU call.
+ * Errors: DS_ERR_NULL, DS_ERR_BAD_W, DS_ERR_BAD_SIZES.
+ */
+int ds_partition(uint64_t seed, uint64_t t, int32_t W, const int32_t* sizes, int32_t n_groups,
+                 int32_t* perm_out, int32_t* off_out);
+
+/*
+ * ds_group_sync -- local SGD update fused with the in-group parameter average.
+ *
+ * Paper: Listing 1, optimizer.step() followed by Average(model, group);
+ * Sec. III-A step 4 (parameters are averaged within the group after the local
+ * update); Sec. IV-B2, X_{k+1} = W_k X_k with w_ij = 1/|group|.
+ * For every group g and column p < P:
+ *     m = (1/|g|) * sum_{i in g} ( X[i,p] - lr * G[i,p] );   X[i,p] = m for all i in g
+ * One value is computed per (group, column) and stored |g| times, so the rows
+ * of a group are bit-identical afterwards.  fp32 arithmetic; bf16 gradients
+ * are widened exactly.  Each replica element is read once and written once.
+ *
+ *   X        dev fp32 [W, ldx], in/out, updated in place
+ *   G        dev [W, ldg], fp32 (DS_F32) or bf16 (DS_BF16), read only,
+ *            must not overlap X
+ *   P        columns to process, >= 0 (0 enqueues nothing)
+ *   ldx,ldg  leading dimensions in elements, >= P, multiples of 4
+ *   perm,off host; any valid division of the workers (as ds_partition writes it,
+ *            or any other: the call does not care how the groups were chosen)
+ *   lr       learning rate
+ * Alignment: X and G 16-byte aligned.
+ * Errors: DS_ERR_NULL, DS_ERR_BAD_W, DS_ERR_BAD_SIZES, DS_ERR_BAD_PART,
+ *         DS_ERR_BAD_SHAPE, DS_ERR_ALIGN, DS_ERR_DTYPE, DS_ERR_HIP.
+ */
+int ds_group_sync(void* X, const void* G, int32_t g_dtype, int64_t P, int64_t ldx, int64_t ldg,
+                  int32_t W, const int32_t* perm, const int32_t* off, int32_t n_groups, float lr,
+                  void* stream);
+
+/*
+ * Ragged variant: the same step over S column segments of the stacks in ONE
+ * launch.  Paper: Sec. V-A1 (parameters are synchronised layer by layer) and
+ * Sec. IV-A (the model is synchronised L times per iteration); a segment is
+ * one layer's slice of every replica.  Columns outside the segments are left
+ * untouched.
+ *
+ * A segment is columns offset .. offset+length-1 of every row.  Rules: length
+ * >= 0 (empty segments are allowed), offset >= 0 and a multiple of 8 elements,
+ * offset+length <= min(ldx, ldg), segments pairwise disjoint.
+ *
+ * The segment list is turned once into a device-side tile table ("plan"):
+ *   ds_ragged_plan_bytes   bytes the plan needs (0 if every segment is empty)
+ *   ds_ragged_plan         builds the table on the host, copies it to `plan`
+ *                          on `stream` and WAITS for the copy (set-up call,
+ *                          once per layer list)
+ *   ds_group_sync_ragged   kernel launch only; `segs`/`S` must be the list the
+ *                          plan was built from (only its tile count is re-derived)
+ * plan: dev, 16-byte aligned, at least ds_ragged_plan_bytes bytes.
+ * Other arguments, alignment and errors as ds_group_sync; a bad segment table
+ * is DS_ERR_BAD_SHAPE (or DS_ERR_ALIGN for an offset), a bad plan buffer
+ * DS_ERR_WORKSPACE.
+ */
+typedef struct {
+    int64_t offset;  /* first column, in elements */
+    int64_t length;  /* number of columns         */
+} ds_segment;
+
+size_t ds_ragged_plan_bytes(const ds_segment* segs, int32_t S);
+
+int ds_ragged_plan(const ds_segment* segs, int32_t S, int64_t ldx, int64_t ldg, void* plan,
+                   size_t plan_bytes, void* stream);
+
+int ds_group_sync_ragged(void* X, const void* G, int32_t g_dtype, const ds_segment* segs, int32_t S,
+                         int64_t ldx, int64_t ldg, int32_t W, const int32_t* perm,
+                         const int32_t* off, int32_t n_groups, float lr, const void* plan,
+                         size_t plan_bytes, void* stream);
+
+/*
+ * ds_consensus -- how far every replica is from the mean replica.
+ *
+ * Paper: Sec. IV-B2; the left-hand side of Lemma 1 for worker i, un-squared:
+ *     xbar[p] = (1/W) * sum_i X[i,p];   dev_out[i] = sqrt( sum_{p<P} (X[i,p] - xbar[p])^2 )
+ * The column mean and the differences are formed in fp64, so identical
+ * replicas give exactly 0.  The result is deterministic (fixed reduction
+ * tree, no floating-point atomics).  X is read once.
+ *
+ *   X          dev fp32 [W, ld], read only; 16-byte aligned, ld >= P, ld % 4 == 0
+ *   dev_out    dev fp64 [W], written
+ *   workspace  dev, 16-byte aligned, >= ds_consensus_workspace_bytes(W, P) bytes,
+ *              overwritten (per-block partial sums)
+ * P == 0 writes zeros.
+ * Errors: DS_ERR_NULL, DS_ERR_BAD_W, DS_ERR_BAD_SHAPE, DS_ERR_ALIGN,
+ *         DS_ERR_WORKSPACE, DS_ERR_HIP.
+ */
+size_t ds_consensus_workspace_bytes(int32_t W, int64_t P);
+
+int ds_consensus(const void* X, int64_t P, int64_t ld, int32_t W, double* dev_out, void* workspace,
+                 size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DSSYNC_H */

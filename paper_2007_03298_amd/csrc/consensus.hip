@@ -1,0 +1,173 @@
+// Consensus-deviation kernels for gfx950: d_i = || x_i - mean_j x_j ||_2 for
+// every worker i (Sec. IV-B2; the left-hand side of Lemma 1, un-squared).
+//
+// A read-only streaming pass, bound by HBM bandwidth (4 bytes per (worker,
+// column), a handful of ALU operations on them).  Mapping:
+//   - a lane loads its kVec consecutive columns of ALL W rows into registers
+//     (one 128-bit or 64-bit load per row, coalesced across the wavefront), so
+//     X is read exactly once;
+//   - the column mean is formed in fp64 and split into an fp32 pair hi + lo;
+//     the difference (x_i - hi) - lo is then plain fp32 work whose rounding
+//     error is relative to the difference itself (and exactly zero for
+//     identical replicas); it is squared and summed into one fp32 accumulator
+//     per worker per lane;
+//   - workgroups walk the column tiles with a grid stride; at the end the lane
+//     accumulators are widened to fp64, reduced across the wavefront with
+//     lane shuffles, across the 4 wavefronts through LDS, and written as one
+//     partial row per workgroup;
+//   - a second kernel adds the partial rows in a fixed order and takes the
+//     square root.  No floating-point atomics: the result is deterministic.
+#include <hip/hip_runtime.h>
+
+#include "ds_internal.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
+constexpr int kMaxBlocks = 2048;  // upper bound of the grid of the partial kernel
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+template <int kVec> struct VecOf;
+template <> struct VecOf<4> { typedef f32x4 type; };
+template <> struct VecOf<2> { typedef f32x2 type; };
+
+__host__ __device__ constexpr int padded_w(int W) { return W <= 8 ? 8 : W <= 16 ? 16 : W <= 32 ? 32 : 64; }
+
+template <int kWPad, int kVec>
+__global__ void __launch_bounds__(kThreads)
+consensus_partial_kernel(const float* __restrict__ X, int64_t P, int64_t ld, int W,
+                         double* __restrict__ partial) {
+    typedef typename VecOf<kVec>::type vec_t;
+    constexpr int kTileCols = kThreads * kVec;
+    float acc[kWPad];
+#pragma unroll
+    for (int i = 0; i < kWPad; ++i) acc[i] = 0.f;
+
+    const int64_t n_tiles = (P + kTileCols - 1) / kTileCols;
+    const double wd = static_cast<double>(W);
+    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const int64_t c = tile * kTileCols + static_cast<int64_t>(threadIdx.x) * kVec;
+        vec_t row[kWPad];
+        if (c + kVec <= P) {
+#pragma unroll
+            for (int i = 0; i < kWPad; ++i)
+                if (i < W) row[i] = *reinterpret_cast<const vec_t*>(X + i * ld + c);
+        } else {
+            // last, partial vector of the row: columns at or beyond P count as 0 in
+            // every row, which adds nothing to any deviation
+#pragma unroll
+            for (int i = 0; i < kWPad; ++i) {
+                if (i < W) {
+#pragma unroll
+                    for (int e = 0; e < kVec; ++e) row[i][e] = (c + e < P) ? X[i * ld + c + e] : 0.f;
+                }
+            }
+        }
+        double mean[kVec];
+#pragma unroll
+        for (int e = 0; e < kVec; ++e) mean[e] = 0.0;
+#pragma unroll
+        for (int i = 0; i < kWPad; ++i) {
+            if (i < W) {
+#pragma unroll
+                for (int e = 0; e < kVec; ++e) mean[e] += static_cast<double>(row[i][e]);
+            }
+        }
+        // mean as an unevaluated fp32 pair hi + lo (|lo| <= ulp(hi)/2): subtracting
+        // hi, then lo, in fp32 leaves an error that is relative to the difference
+        // itself, and is exactly 0 when every row equals the mean
+        float hi[kVec], lo[kVec];
+#pragma unroll
+        for (int e = 0; e < kVec; ++e) {
+            const double m = mean[e] / wd;
+            hi[e] = static_cast<float>(m);
+            lo[e] = static_cast<float>(m - static_cast<double>(hi[e]));
+        }
+#pragma unroll
+        for (int i = 0; i < kWPad; ++i) {
+            if (i < W) {
+#pragma unroll
+                for (int e = 0; e < kVec; ++e) {
+                    const float d = (row[i][e] - hi[e]) - lo[e];
+                    acc[i] = __builtin_fmaf(d, d, acc[i]);
+                }
+            }
+        }
+    }
+
+    // lanes -> wavefront -> workgroup, in fp64
+    __shared__ double wave_sum[kWaves][kWPad];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int i = 0; i < kWPad; ++i) {
+        double v = static_cast<double>(acc[i]);
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+        if (lane == 0) wave_sum[wave][i] = v;
+    }
+    __syncthreads();
+    if (threadIdx.x < kWPad) {
+        double v = 0.0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) v += wave_sum[w][threadIdx.x];
+        partial[static_cast<int64_t>(blockIdx.x) * kWPad + threadIdx.x] = v;
+    }
+}
+
+// one workgroup per worker: fixed-order sum of its column of the partial rows
+__global__ void __launch_bounds__(kThreads)
+consensus_final_kernel(const double* __restrict__ partial, int n_rows, int w_pad, double* __restrict__ out) {
+    __shared__ double buf[kThreads];
+    const int i = blockIdx.x;
+    double v = 0.0;
+    for (int b = threadIdx.x; b < n_rows; b += kThreads) v += partial[static_cast<int64_t>(b) * w_pad + i];
+    buf[threadIdx.x] = v;
+    __syncthreads();
+    for (int half = kThreads / 2; half >= 1; half >>= 1) {
+        if (static_cast<int>(threadIdx.x) < half) buf[threadIdx.x] += buf[threadIdx.x + half];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) out[i] = sqrt(buf[0]);
+}
+
+}  // namespace
+
+extern "C" size_t ds_consensus_workspace_bytes(int32_t W, int64_t P) {
+    if (W < 1 || W > DS_MAX_W || P < 0) return 0;
+    return static_cast<size_t>(kMaxBlocks) * static_cast<size_t>(padded_w(W)) * sizeof(double);
+}
+
+extern "C" int ds_consensus(const void* X, int64_t P, int64_t ld, int32_t W, double* dev_out,
+                            void* workspace, size_t workspace_bytes, void* stream) {
+    if (!X || !dev_out) return DS_ERR_NULL;
+    if (W < 1 || W > DS_MAX_W) return DS_ERR_BAD_W;
+    if (P < 0 || ld < P) return DS_ERR_BAD_SHAPE;
+    if (!ds::aligned16(X) || ld % 4 != 0 || (reinterpret_cast<uintptr_t>(dev_out) & 7u) != 0) return DS_ERR_ALIGN;
+    if (!workspace || !ds::aligned16(workspace) || workspace_bytes < ds_consensus_workspace_bytes(W, P))
+        return DS_ERR_WORKSPACE;
+
+    const int w_pad = padded_w(W);
+    const int vec = w_pad == 64 ? 2 : 4;
+    const int64_t tile_cols = static_cast<int64_t>(kThreads) * vec;
+    const int64_t n_tiles = (P + tile_cols - 1) / tile_cols;
+    // at least one workgroup, so that P == 0 still writes a (zero) partial row
+    const int n_blocks = static_cast<int>(n_tiles < 1 ? 1 : (n_tiles < kMaxBlocks ? n_tiles : kMaxBlocks));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const float* x = static_cast<const float*>(X);
+    double* partial = static_cast<double*>(workspace);
+    const dim3 grid(static_cast<uint32_t>(n_blocks)), block(kThreads);
+    switch (w_pad) {
+        case 8: hipLaunchKernelGGL((consensus_partial_kernel<8, 4>), grid, block, 0, st, x, P, ld, W, partial); break;
+        case 16: hipLaunchKernelGGL((consensus_partial_kernel<16, 4>), grid, block, 0, st, x, P, ld, W, partial); break;
+        case 32: hipLaunchKernelGGL((consensus_partial_kernel<32, 4>), grid, block, 0, st, x, P, ld, W, partial); break;
+        default: hipLaunchKernelGGL((consensus_partial_kernel<64, 2>), grid, block, 0, st, x, P, ld, W, partial); break;
+    }
+    if (hipGetLastError() != hipSuccess) return DS_ERR_HIP;
+    hipLaunchKernelGGL(consensus_final_kernel, dim3(static_cast<uint32_t>(W)), block, 0, st, partial, n_blocks,
+                       w_pad, dev_out);
+    return hipGetLastError() == hipSuccess ? DS_OK : DS_ERR_HIP;
+}

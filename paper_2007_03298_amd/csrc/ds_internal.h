@@ -1,0 +1,42 @@
+// Internal declarations shared by the translation units of libdssync.
+#pragma once
+
+#include <stdint.h>
+
+#include "dssync.h"
+
+namespace ds {
+
+// Division of the workers as the kernels see it: member rows of group k are
+// perm[off[k]] .. perm[off[k+1]-1].  Passed by value in the kernel-argument
+// block (132 bytes), so the device reads it through the scalar cache and no
+// host-to-device copy is needed.
+struct PartitionArg {
+    uint8_t perm[DS_MAX_W];
+    uint8_t off[DS_MAX_W + 4];  // n_groups+1 entries used
+};
+
+// Checks perm/off (host arrays) and packs them; returns DS_OK or the status to
+// hand back to the caller.  max_size receives the largest group size and
+// equal_size the common size if all groups are equal (else 0).
+int pack_partition(int32_t W, const int32_t* perm, const int32_t* off, int32_t n_groups,
+                   PartitionArg* out, int32_t* max_size, int32_t* equal_size);
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Columns handled by one workgroup of the group-sync kernels: 256 lanes, each
+// owning kSyncVecPerLane vectors of 4 consecutive columns.  The ragged plan is
+// cut in the same unit.
+constexpr int kSyncThreads = 256;
+constexpr int kSyncVecPerLane = 2;
+constexpr int kSyncTileCols = kSyncThreads * 4 * kSyncVecPerLane;
+
+// One entry of the ragged plan: a run of at most kSyncTileCols columns that
+// lies inside one segment and starts on a multiple of 8 columns.
+struct Tile {
+    int64_t start;
+    int32_t len;
+    int32_t pad;
+};
+
+}  // namespace ds

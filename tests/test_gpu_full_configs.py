@@ -1,0 +1,171 @@
+"""GPU parity at the full benchmark sizes, in the launch configuration that
+``bench.py`` times.  The oracle cannot afford whole stacks of tens of GB, but
+columns never interact (the mixing matrix acts on the worker axis only,
+Sec. IV-B2), so parity on sampled column windows is exact parity for those
+columns: the windows' inputs are copied to the host, the oracle runs the same
+T iterations on them (keeping its own state: trajectory parity) and is also
+applied to the GPU's own pre-step state (per-step parity).  The consensus
+norms depend on every column; they are checked on column chunks against the
+oracle, by additivity of the squared norms over chunks, and - where the stack
+fits the host comfortably - against the oracle on the whole stack.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2007_03298_amd as ds
+from paper_2007_03298_amd import workloads as wl
+from test_gpu_parity import (DEV, TOL_BF16, TOL_F32, assert_members_identical, gpu_consensus, scaled_error)
+
+pytestmark = pytest.mark.gpu
+
+
+def window_columns(P, ld, rng, n_random=24, width=512, edge=4096):
+    cols = [np.arange(0, min(edge, P)), np.arange(max(0, P - edge - 3), P)]
+    for _ in range(n_random):
+        c0 = int(rng.integers(0, max(1, P - width)))
+        cols.append(np.arange(c0, min(P, c0 + width)))
+    return np.unique(np.concatenate(cols))
+
+
+def consensus_chunk(X, c0, n, ld, W):
+    view = X[:, c0:]                                   # same storage, shifted base (c0 % 4 == 0)
+    assert view.data_ptr() % 16 == 0
+    return gpu_consensus(view, n, ld, W)
+
+
+def run_flat_config(idx, full_consensus):
+    cfg = wl.CONFIGS[idx]
+    W, P = cfg.W, cfg.P
+    free, _ = torch.cuda.mem_get_info()
+    need = 2 * W * P * 4 + (2 << 30)
+    if free < need:
+        pytest.skip("needs %.1f GB of free HBM" % (need / 1e9))
+    print("config", idx, cfg.name, flush=True)
+    run = wl.Run(cfg, DEV)
+    X = run.init_params()
+    rng = np.random.default_rng(1000 + idx)
+    cols = window_columns(P, P, rng)
+    cols_t = torch.from_numpy(cols).to(DEV)
+    Xo = X.index_select(1, cols_t).cpu().numpy()       # oracle's own state on the windows
+    G = torch.empty(W, P, dtype=torch.float32, device=DEV)
+    worst_step = worst_traj = 0.0
+    for t in range(cfg.T):
+        run.gradients(out=G)
+        perm, off = ds.ds_partition(cfg.seed, t, W, cfg.sizes)
+        po, oo = oracle.partition(cfg.seed, t, W, cfg.sizes)
+        assert perm.tolist() == po.tolist() and off.tolist() == oo.tolist()
+        before = X.index_select(1, cols_t).cpu().numpy()
+        Gw = G.index_select(1, cols_t).cpu().numpy()
+        ds.ds_group_sync(X, G, ds.DS_F32, P, P, P, W, perm, off, cfg.lr)
+        torch.cuda.synchronize()
+        got = X.index_select(1, cols_t).cpu().numpy()
+        oracle.step(before, Gw, po, oo, cfg.lr)
+        oracle.step(Xo, Gw, po, oo, cfg.lr)
+        worst_step = max(worst_step, scaled_error(got, before))
+        worst_traj = max(worst_traj, scaled_error(got, Xo))
+        assert_members_identical(got, perm, off)
+        print("  t=%d step err %.2e traj err %.2e" % (t, worst_step, worst_traj), flush=True)
+    assert worst_step <= TOL_F32 and worst_traj <= TOL_F32
+    del G
+    # members identical over ALL columns, checked on the device
+    for k in range(len(off) - 1):
+        members = perm[off[k]:off[k + 1]]
+        ref = X[int(members[0])].view(torch.int32)
+        for i in members[1:]:
+            assert torch.equal(ref, X[int(i)].view(torch.int32))
+
+    # consensus: chunks against the oracle, additivity, and (optionally) the whole stack
+    d_full = gpu_consensus(X, P, P, W)
+    q = (P // 4) // 4 * 4
+    edges = [0, q, 2 * q + 4, 3 * q, P]
+    sq = np.zeros(W)
+    for a, b in zip(edges[:-1], edges[1:]):
+        sq += consensus_chunk(X, a, b - a, P, W) ** 2
+    np.testing.assert_allclose(np.sqrt(sq), d_full, rtol=1e-6)
+    for c0, n in [(0, 1 << 20), (edges[2], (1 << 20) + 1), (P - (1 << 20) - 4, (1 << 20) + 4)]:
+        got = consensus_chunk(X, c0, n, P, W)
+        want = oracle.consensus(np.ascontiguousarray(X[:, c0:c0 + n].cpu().numpy()))
+        np.testing.assert_allclose(got, want, rtol=1e-5)
+    if full_consensus:
+        want = oracle.consensus(X.cpu().numpy())
+        np.testing.assert_allclose(d_full, want, rtol=1e-5)
+    print("  consensus max %.4f" % d_full.max(), flush=True)
+
+
+def test_config2_full_size():
+    run_flat_config(2, full_consensus=True)
+
+
+def test_config3_full_size():
+    run_flat_config(3, full_consensus=True)
+
+
+def test_config4_full_size():
+    run_flat_config(4, full_consensus=False)
+
+
+def test_config5_ragged_full_size():
+    cfg = wl.CONFIGS[5]
+    W = cfg.W
+    segs, ld, attempt = wl.ragged_segments(cfg.seed)
+    total = sum(n for _, n in segs)
+    print("config 5:", len(segs), "segments, total", total, "ld", ld, "attempt", attempt, flush=True)
+    assert len(segs) == 199 and 99_000_000 <= total <= 121_000_000
+    run = wl.Run(cfg, DEV, P=ld, ld=ld)
+    X = run.init_params()
+    rng = np.random.default_rng(1005)
+    # windows: both ends of a sample of segments (with the padding gap after them) and random interiors
+    cols = []
+    for s in rng.choice(len(segs), 40, replace=False).tolist() + [0, len(segs) - 1]:
+        o, n = segs[s]
+        cols.append(np.arange(o, min(o + 300, o + n)))
+        cols.append(np.arange(max(o, o + n - 300), min(ld, o + n + 64)))
+        if n > 5000:
+            c0 = o + int(rng.integers(0, n - 600))
+            cols.append(np.arange(c0, c0 + 600))
+    cols = np.unique(np.concatenate(cols))
+    in_seg = np.zeros(ld, dtype=bool)
+    for o, n in segs:
+        in_seg[o:o + n] = True
+    live = in_seg[cols]
+    cols_t = torch.from_numpy(cols).to(DEV)
+    Xo = X.index_select(1, cols_t).cpu().numpy()
+    start = Xo.copy()
+
+    nbytes = ds.ds_ragged_plan_bytes(segs)
+    plan = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    ds.ds_ragged_plan(segs, ld, ld, plan, nbytes)
+    packed = ds.pack_segments(segs)
+    G = torch.empty(W, ld, dtype=torch.bfloat16, device=DEV)
+    worst_step = worst_traj = 0.0
+    for t in range(cfg.T):
+        run.gradients(out=G)
+        perm, off = ds.ds_partition(cfg.seed, t, W, cfg.sizes)
+        po, oo = oracle.partition(cfg.seed, t, W, cfg.sizes)
+        assert perm.tolist() == po.tolist() and off.tolist() == oo.tolist()
+        before = X.index_select(1, cols_t).cpu().numpy()
+        Gw = wl.tensor_to_numpy(G.index_select(1, cols_t))
+        ds.ds_group_sync_ragged(X, G, ds.DS_BF16, packed, ld, ld, W, perm, off, cfg.lr, plan, nbytes)
+        torch.cuda.synchronize()
+        got = X.index_select(1, cols_t).cpu().numpy()
+        # the oracle steps only the sampled columns that lie inside a segment
+        b_live, o_live = np.ascontiguousarray(before[:, live]), np.ascontiguousarray(Xo[:, live])
+        g_live = np.ascontiguousarray(Gw[:, live])
+        oracle.step(b_live, g_live, po, oo, cfg.lr)
+        oracle.step(o_live, g_live, po, oo, cfg.lr)
+        Xo[:, live] = o_live
+        worst_step = max(worst_step, scaled_error(got[:, live], b_live))
+        worst_traj = max(worst_traj, scaled_error(got[:, live], o_live))
+        assert np.array_equal(got[:, ~live], start[:, ~live])           # padding never written
+        assert_members_identical(got[:, live], perm, off)
+        print("  t=%d step err %.2e traj err %.2e" % (t, worst_step, worst_traj), flush=True)
+    assert worst_step <= TOL_BF16 and worst_traj <= TOL_BF16
+    # the stated bf16 bar is loose; the arithmetic is the fp32 path's, so hold it to that as well
+    assert worst_step <= TOL_F32
+    d = gpu_consensus(X, ld, ld, W)
+    c0, n = segs[100][0], min(segs[100][1], 1 << 20)
+    np.testing.assert_allclose(consensus_chunk(X, c0, n, ld, W),
+                               oracle.consensus(np.ascontiguousarray(X[:, c0:c0 + n].cpu().numpy())), rtol=1e-5)
+    assert d.min() > 0

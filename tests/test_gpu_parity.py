@@ -1,0 +1,274 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on
+the same seeded inputs.
+
+Bars (fp32 replica arithmetic on the GPU, fp64 in the oracle):
+  * worker division: bit exact;
+  * members of a group after a step: bit identical;
+  * replica elements: |gpu - oracle| <= 1e-5 * max(|oracle|, rms(oracle row))
+    (2e-3 with bf16 gradients).  The denominator keeps the bound meaningful for
+    elements near zero.  fp32 error budget per step: one rounding per local
+    update, |g|-1 additions, one division -> about (|g|+2)/2 ulp of the
+    largest partial sum, i.e. below 1e-6 of the row scale for |g| <= 64;
+  * consensus norms: relative error <= 1e-5, exactly 0 for identical replicas.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2007_03298_amd as ds
+from paper_2007_03298_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+TOL_F32 = 1e-5
+TOL_BF16 = 2e-3
+
+
+def scaled_error(got: np.ndarray, want: np.ndarray) -> float:
+    """max |got-want| / max(|want|, rms(want row)) over a [W, n] block."""
+    want64 = want.astype(np.float64)
+    rms = np.sqrt((want64**2).mean(axis=1, keepdims=True))
+    den = np.maximum(np.abs(want64), np.maximum(rms, 1e-30))
+    return float((np.abs(got.astype(np.float64) - want64) / den).max()) if want.size else 0.0
+
+
+def assert_members_identical(Xh: np.ndarray, perm, off):
+    bits = Xh.view(np.uint32)
+    for k in range(len(off) - 1):
+        members = perm[off[k]:off[k + 1]]
+        for i in members[1:]:
+            assert np.array_equal(bits[members[0]], bits[i])
+
+
+def gpu_consensus(X: torch.Tensor, P: int, ld: int, W: int) -> np.ndarray:
+    need = ds.ds_consensus_workspace_bytes(W, P)
+    ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+    out = torch.full((W,), -1.0, dtype=torch.float64, device=DEV)
+    ds.ds_consensus(X, P, ld, W, out, ws, need)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def random_stacks(seed, W, ldx, ldg, bf16):
+    g = torch.Generator(device=DEV)
+    g.manual_seed(seed)
+    X = torch.empty(W, ldx, dtype=torch.float32, device=DEV).normal_(0, 0.02, generator=g)
+    G = torch.empty(W, ldg, dtype=torch.float32, device=DEV).normal_(generator=g)
+    if bf16:
+        G = G.to(torch.bfloat16)
+    return X, G
+
+
+# ---------------------------------------------------------------- small, element by element
+
+SMALL = [
+    # W, sizes, P, ldx, ldg
+    (8, [4, 4], 2048 * 3 + 517, None, None),          # several tiles and a ragged end
+    (8, [2, 3, 3], 5000, 5004, 5008),                 # the paper's two-rack division, padded rows
+    (8, [8], 4099, None, None),                       # one group: BSP
+    (8, [1] * 8, 4097, None, None),                   # groups of one: independent SGD
+    (5, [1, 4], 1, None, None),
+    (3, [3], 2, None, None),
+    (7, [3, 4], 3, None, None),
+    (16, [4] * 4, 2047, None, None),
+    (16, [5, 11], 2049, None, None),                  # more members than one round of loads
+    (32, [8] * 4, 10000, None, None),
+    (64, [8] * 8, 3000, None, None),
+    (64, [64], 2500, None, None),
+    (64, [1] * 63 + [1], 300, None, None),
+    (1, [1], 777, None, None),
+]
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("W,sizes,P,ldx,ldg", SMALL)
+def test_step_matches_oracle_small(W, sizes, P, ldx, ldg, bf16):
+    ldx = ldx or (P + 3) // 4 * 4
+    ldg = ldg or (P + 3) // 4 * 4
+    X, G = random_stacks(100 + W + P, W, ldx, ldg, bf16)
+    Xh0, Gh = wl.tensor_to_numpy(X), wl.tensor_to_numpy(G)
+    for t in range(3):
+        perm, off = ds.ds_partition(5, t, W, sizes)
+        po, oo = oracle.partition(5, t, W, sizes)
+        assert perm.tolist() == po.tolist() and off.tolist() == oo.tolist()
+        before = wl.tensor_to_numpy(X)
+        ds.ds_group_sync(X, G, ds.DS_BF16 if bf16 else ds.DS_F32, P, ldx, ldg, W, perm, off, 0.01)
+        torch.cuda.synchronize()
+        got = wl.tensor_to_numpy(X)
+        want = before.copy()
+        oracle.step(want, Gh, po, oo, 0.01, 0, P)
+        assert scaled_error(got[:, :P], want[:, :P]) <= (TOL_BF16 if bf16 else TOL_F32)
+        assert np.array_equal(got[:, P:], before[:, P:])          # padding columns untouched
+        assert_members_identical(got[:, :P], perm, off)
+    assert not np.array_equal(got[:, :P], Xh0[:, :P])
+
+
+def test_group_of_all_workers_is_mean_gradient_sgd_on_gpu():
+    W, P = 16, 6001
+    ld = 6004
+    X, G = random_stacks(7, W, ld, ld, False)
+    xm = X[:, :P].double().mean(0)
+    gm = G[:, :P].double().mean(0)
+    perm, off = ds.ds_partition(0, 0, W, [W])
+    ds.ds_group_sync(X, G, ds.DS_F32, P, ld, ld, W, perm, off, 0.05)
+    torch.cuda.synchronize()
+    want = (xm - float(np.float32(0.05)) * gm).cpu().numpy()
+    got = X[:, :P].cpu().numpy()
+    assert scaled_error(got, np.tile(want, (W, 1)).astype(np.float32)) <= TOL_F32
+    assert np.array_equal(gpu_consensus(X, P, ld, W), np.zeros(W))
+
+
+def test_bf16_path_equals_fp32_path_on_widened_gradients():
+    W, P = 8, 9001
+    ld = 9004
+    X, G = random_stacks(8, W, ld, ld, True)
+    X2 = X.clone()
+    perm, off = ds.ds_partition(3, 1, W, [4, 4])
+    ds.ds_group_sync(X, G, ds.DS_BF16, P, ld, ld, W, perm, off, 0.01)
+    ds.ds_group_sync(X2, G.float(), ds.DS_F32, P, ld, ld, W, perm, off, 0.01)
+    torch.cuda.synchronize()
+    assert torch.equal(X, X2)          # widening is exact, so the two paths agree bit for bit
+
+
+def test_empty_step_enqueues_nothing():
+    X, G = random_stacks(9, 8, 16, 16, False)
+    before = X.clone()
+    ds.ds_group_sync(X, G, ds.DS_F32, 0, 16, 16, 8, list(range(8)), [0, 4, 8], 0.01)
+    torch.cuda.synchronize()
+    assert torch.equal(X, before)
+
+
+# ---------------------------------------------------------------- ragged
+
+def check_ragged(W, sizes, segs, ld, bf16, seed):
+    X, G = random_stacks(seed, W, ld, ld, bf16)
+    Gh = wl.tensor_to_numpy(G)
+    nbytes = ds.ds_ragged_plan_bytes(segs)
+    plan = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=DEV)
+    ds.ds_ragged_plan(segs, ld, ld, plan, nbytes)
+    packed = ds.pack_segments(segs)
+    for t in range(2):
+        perm, off = ds.ds_partition(4, t, W, sizes)
+        before = wl.tensor_to_numpy(X)
+        ds.ds_group_sync_ragged(X, G, ds.DS_BF16 if bf16 else ds.DS_F32, packed, ld, ld, W, perm, off, 0.01,
+                                plan, nbytes)
+        torch.cuda.synchronize()
+        got = wl.tensor_to_numpy(X)
+        want = before.copy()
+        po, oo = oracle.partition(4, t, W, sizes)
+        for o, n in segs:
+            oracle.step(want, Gh, po, oo, 0.01, o, n)
+        assert scaled_error(got, want) <= (TOL_BF16 if bf16 else TOL_F32)
+        covered = np.zeros(ld, dtype=bool)
+        for o, n in segs:
+            covered[o:o + n] = True
+        assert np.array_equal(got[:, ~covered], before[:, ~covered])   # gaps untouched
+        assert_members_identical(got[:, covered], perm, off)
+
+
+@pytest.mark.parametrize("bf16", [True, False])
+def test_ragged_matches_oracle_small(bf16):
+    segs = [(0, 256), (256, 1), (264, 0), (320, 2047), (2368, 2048), (4416, 2049), (6472, 7), (6528, 5000),
+            (16384, 3)]
+    check_ragged(8, [4, 4], segs, 16392, bf16, 21)
+    check_ragged(8, [2, 3, 3], segs[::-1], 16392, bf16, 22)          # any order of the list
+    check_ragged(32, [4] * 8, [(128 * i, 61 + i) for i in range(40)], 128 * 41, bf16, 23)
+
+
+def test_ragged_equals_flat_on_one_segment():
+    W, P, ld = 8, 50000, 50000
+    X, G = random_stacks(24, W, ld, ld, True)
+    X2 = X.clone()
+    perm, off = ds.ds_partition(1, 1, W, [4, 4])
+    segs = [(0, P)]
+    nbytes = ds.ds_ragged_plan_bytes(segs)
+    plan = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    ds.ds_ragged_plan(segs, ld, ld, plan, nbytes)
+    ds.ds_group_sync_ragged(X, G, ds.DS_BF16, segs, ld, ld, W, perm, off, 0.01, plan, nbytes)
+    ds.ds_group_sync(X2, G, ds.DS_BF16, P, ld, ld, W, perm, off, 0.01)
+    torch.cuda.synchronize()
+    assert torch.equal(X, X2)
+
+
+# ---------------------------------------------------------------- consensus
+
+@pytest.mark.parametrize("W,P,ld", [(8, 1, 4), (8, 1023, 1024), (8, 100003, 100004), (5, 7777, 7780),
+                                    (16, 50001, 50004), (13, 4096, 4096), (32, 30001, 30004),
+                                    (33, 9999, 10000), (64, 20001, 20004), (1, 5000, 5000),
+                                    (32, 2_100_000, 2_100_000)])
+def test_consensus_matches_oracle(W, P, ld):
+    X, _ = random_stacks(31 + W, W, ld, 4, False)
+    got = gpu_consensus(X, P, ld, W)
+    want = oracle.consensus(wl.tensor_to_numpy(X), P)
+    if W == 1:
+        assert np.array_equal(got, np.zeros(1))
+    else:
+        np.testing.assert_allclose(got, want, rtol=1e-5, atol=0)
+
+
+def test_consensus_of_nearly_identical_replicas():
+    # replicas that differ in the last bits only: the deviation is tiny against the
+    # values, and must still be accurate relative to itself
+    W, P = 8, 40000
+    X, _ = random_stacks(41, 1, P, 4, False)
+    X = X.repeat(W, 1).contiguous()
+    Xi = X.view(torch.int32)
+    bump = torch.randint(0, 3, (W, P), device=DEV, dtype=torch.int32,
+                         generator=torch.Generator(device=DEV).manual_seed(1))
+    Xi += bump
+    got = gpu_consensus(X, P, P, W)
+    want = oracle.consensus(wl.tensor_to_numpy(X), P)
+    assert want.min() > 0
+    np.testing.assert_allclose(got, want, rtol=1e-5, atol=0)
+
+
+def test_consensus_zero_for_identical_replicas_and_empty_input():
+    for W in (3, 8, 24, 64):
+        X, _ = random_stacks(51, 1, 5000, 4, False)
+        X = X.repeat(W, 1).contiguous()
+        assert np.array_equal(gpu_consensus(X, 5000, 5000, W), np.zeros(W))
+    X, _ = random_stacks(52, 8, 16, 4, False)
+    assert np.array_equal(gpu_consensus(X, 0, 16, 8), np.zeros(8))
+
+
+def test_consensus_is_deterministic():
+    X, _ = random_stacks(53, 32, 300000, 4, False)
+    a = gpu_consensus(X, 300000, 300000, 32)
+    b = gpu_consensus(X, 300000, 300000, 32)
+    assert np.array_equal(a, b)
+
+
+# ---------------------------------------------------------------- configuration 1: whole trajectory
+
+def test_config1_trajectory_and_consensus():
+    cfg = wl.CONFIGS[1]
+    run = wl.Run(cfg, DEV)
+    X = run.init_params()
+    Xo = wl.tensor_to_numpy(X)                       # the oracle keeps its own state for all T
+    assert np.array_equal(gpu_consensus(X, cfg.P, cfg.P, cfg.W), np.zeros(cfg.W))   # identical start
+    worst_step, worst_traj = 0.0, 0.0
+    for t in range(cfg.T):
+        G = run.gradients()
+        Gh = wl.tensor_to_numpy(G)
+        perm, off = ds.ds_partition(cfg.seed, t, cfg.W, cfg.sizes)
+        po, oo = oracle.partition(cfg.seed, t, cfg.W, cfg.sizes)
+        assert perm.tolist() == po.tolist() and off.tolist() == oo.tolist()
+        before = wl.tensor_to_numpy(X)
+        ds.ds_group_sync(X, G, ds.DS_F32, cfg.P, cfg.P, cfg.P, cfg.W, perm, off, cfg.lr)
+        torch.cuda.synchronize()
+        got = wl.tensor_to_numpy(X)
+        oracle.step(before, Gh, po, oo, cfg.lr)      # per step: oracle applied to the GPU's own state
+        oracle.step(Xo, Gh, po, oo, cfg.lr)          # trajectory: oracle's own state
+        worst_step = max(worst_step, scaled_error(got, before))
+        worst_traj = max(worst_traj, scaled_error(got, Xo))
+        assert_members_identical(got, perm, off)
+        if t == 0:
+            # closed-form expectation after the first step from identical models:
+            # E d_i^2 = P lr^2 0.25 (1/|g| - 1/W)
+            d = gpu_consensus(X, cfg.P, cfg.P, cfg.W)
+            expect = np.sqrt(cfg.P * cfg.lr**2 * 0.25 * (1.0 / cfg.group - 1.0 / cfg.W))
+            np.testing.assert_allclose(d, expect, rtol=0.01)
+    assert worst_step <= TOL_F32 and worst_traj <= TOL_F32
+    np.testing.assert_allclose(gpu_consensus(X, cfg.P, cfg.P, cfg.W), oracle.consensus(Xo), rtol=1e-5)

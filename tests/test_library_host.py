@@ -1,0 +1,170 @@
+"""Host-side checks of libdssync.so that need no GPU: the library loads, exports
+every symbol the header declares, its worker division agrees bit for bit with
+the oracle's independent implementation, and every argument error is reported
+before anything touches a device."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2007_03298_amd as ds
+from paper_2007_03298_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "dssync.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ds_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_symbols()
+    assert set(names) == set(binding.EXPORTS)
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_status_strings():
+    for code in range(0, -10, -1):
+        s = ds.status_string(code)
+        assert s.startswith("DS_")
+    assert not ds.status_string(-99).startswith("DS_")
+
+
+def test_partition_golden(partition_golden):
+    _, perms = partition_golden
+    for seed, t, W, want in perms:
+        perm, off = ds.ds_partition(seed, t, W, [W])
+        assert perm.tolist() == want and off.tolist() == [0, W]
+
+
+def test_partition_bit_exact_against_oracle_on_random_inputs():
+    r = np.random.default_rng(2024)
+    for _ in range(10000):
+        W = int(r.integers(1, ds.DS_MAX_W + 1))
+        # random composition of W into groups
+        cuts = sorted(set(r.integers(1, W, size=int(r.integers(0, min(W, 9)))).tolist())) if W > 1 else []
+        edges = [0] + cuts + [W]
+        sizes = [b - a for a, b in zip(edges[:-1], edges[1:])]
+        seed = int(r.integers(0, 2**63)) * 2 + int(r.integers(0, 2))
+        t = int(r.integers(0, 2**63)) if r.random() < 0.2 else int(r.integers(0, 100000))
+        p1, o1 = ds.ds_partition(seed, t, W, sizes)
+        p2, o2 = oracle.partition(seed, t, W, sizes)
+        assert p1.tolist() == p2.tolist() and o1.tolist() == o2.tolist()
+
+
+def test_partition_errors():
+    def status(*a):
+        with pytest.raises(ds.DsError) as e:
+            ds.ds_partition(*a)
+        return e.value.status
+    assert status(0, 0, 0, [1]) == -2
+    assert status(0, 0, ds.DS_MAX_W + 1, [ds.DS_MAX_W + 1]) == -2
+    assert status(0, 0, 8, [4, 3]) == -3
+    assert status(0, 0, 8, [8, 0]) == -3
+    assert status(0, 0, 8, [9, -1]) == -3
+    assert status(0, 0, 8, []) == -3
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    lib.ds_partition.restype = ctypes.c_int
+    assert lib.ds_partition(ctypes.c_uint64(0), ctypes.c_uint64(0), 4, None, 1, None, None) == -1
+
+
+# ---- argument validation of the GPU entry points (nothing is launched) ----------
+
+A = 4096          # a 16-byte aligned stand-in address; never dereferenced because
+B = 1 << 20       # every call below must fail validation first
+PERM8 = list(range(8))
+OFF8 = [0, 4, 8]
+
+
+def sync_status(X=A, G=B, dt=0, P=16, ldx=16, ldg=16, W=8, perm=PERM8, off=OFF8):
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_group_sync(X, G, dt, P, ldx, ldg, W, perm, off, 0.1, stream=0)
+    return e.value.status
+
+
+def test_group_sync_argument_errors():
+    assert sync_status(X=0) == -1
+    assert sync_status(G=0) == -1
+    assert sync_status(dt=2) == -7
+    assert sync_status(P=-1) == -5
+    assert sync_status(P=20) == -5                  # ld < P
+    assert sync_status(ldx=18, P=10) == -6          # ld not a multiple of 4
+    assert sync_status(X=A + 4) == -6
+    assert sync_status(G=B + 8) == -6
+    assert sync_status(W=0, perm=[], off=[0]) == -2
+    assert sync_status(W=65, perm=list(range(65)), off=[0, 65]) == -2
+    assert sync_status(perm=[0, 1, 2, 3, 4, 5, 6, 6]) == -4
+    assert sync_status(perm=[0, 1, 2, 3, 4, 5, 6, 8]) == -4
+    assert sync_status(off=[0, 4, 7]) == -4
+    assert sync_status(off=[0, 4, 4, 8]) == -4      # empty group
+    assert sync_status(off=[1, 4, 8]) == -4
+
+
+def test_group_sync_empty_is_ok_without_a_device():
+    ds.ds_group_sync(A, B, 0, 0, 16, 16, 8, PERM8, OFF8, 0.1, stream=0)   # P == 0: nothing enqueued
+
+
+def ragged_status(segs, X=A, G=B, ldx=4096, ldg=4096, plan=A, plan_bytes=1 << 20):
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_group_sync_ragged(X, G, 1, segs, ldx, ldg, 8, PERM8, OFF8, 0.1, plan, plan_bytes, stream=0)
+    return e.value.status
+
+
+def test_ragged_argument_errors():
+    assert ragged_status([(4, 16)]) == -6           # offset not a multiple of 8
+    assert ragged_status([(0, -1)]) == -5
+    assert ragged_status([(-8, 4)]) == -5
+    assert ragged_status([(4000, 200)]) == -5       # runs past the leading dimension
+    assert ragged_status([(0, 16)], plan=0) == -8
+    assert ragged_status([(0, 16)], plan_bytes=8) == -8
+    assert ragged_status([(0, 16)], plan=A + 8) == -8
+    # all-empty segment lists enqueue nothing and need no plan
+    ds.ds_group_sync_ragged(A, B, 1, [(0, 0), (64, 0)], 4096, 4096, 8, PERM8, OFF8, 0.1, 0, 0, stream=0)
+    ds.ds_group_sync_ragged(A, B, 1, [], 4096, 4096, 8, PERM8, OFF8, 0.1, 0, 0, stream=0)
+
+
+def test_ragged_plan_bytes_and_plan_errors():
+    assert ds.ds_ragged_plan_bytes([]) == 0
+    assert ds.ds_ragged_plan_bytes([(0, 0)]) == 0
+    one = ds.ds_ragged_plan_bytes([(0, 1)])
+    assert one == 16
+    assert ds.ds_ragged_plan_bytes([(0, 2048), (2048, 2049), (8192, 5)]) == 16 * (1 + 2 + 1)
+    assert ds.ds_ragged_plan_bytes([(3, 5)]) == 0   # invalid list
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_ragged_plan([(0, 64), (32, 64)], 4096, 4096, A, 1 << 20, stream=0)   # overlap
+    assert e.value.status == -5
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_ragged_plan([(0, 64)], 4096, 4096, A, 8, stream=0)
+    assert e.value.status == -8
+    ds.ds_ragged_plan([(0, 0)], 4096, 4096, 0, 0, stream=0)   # nothing to build
+
+
+def test_consensus_argument_errors():
+    need = ds.ds_consensus_workspace_bytes(8, 100)
+    assert need > 0 and need % 16 == 0
+    assert ds.ds_consensus_workspace_bytes(0, 100) == 0
+    assert ds.ds_consensus_workspace_bytes(65, 100) == 0
+
+    def status(X=A, P=16, ld=16, W=8, out=B, ws=3 * B, ws_bytes=need):
+        with pytest.raises(ds.DsError) as e:
+            ds.ds_consensus(X, P, ld, W, out, ws, ws_bytes, stream=0)
+        return e.value.status
+    assert status(X=0) == -1
+    assert status(out=0) == -1
+    assert status(W=0) == -2
+    assert status(W=65) == -2
+    assert status(P=-1) == -5
+    assert status(P=17) == -5
+    assert status(ld=18, P=10) == -6
+    assert status(X=A + 4) == -6
+    assert status(out=B + 4) == -6
+    assert status(ws=0) == -8
+    assert status(ws_bytes=need - 1) == -8
+    assert status(ws=3 * B + 8) == -8
