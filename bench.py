@@ -78,6 +78,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=3, help="benchmark configuration (flat fp32 ones: 1-4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--probe-copy", type=int, default=0, metavar="N",
+                    help="also launch the plain copy kernel N times on a stack-sized buffer before the "
+                         "timed region (yardstick for bandwidth and for profiler counter scaling)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (W simulated workers stacked in one HBM); "
@@ -116,6 +119,22 @@ def main() -> int:
         ds.ds_consensus(X, P, P, W, dev_out, ws, ws_bytes, stream)
         if ev:
             ev[2].record(stream)
+
+    probe = None
+    if args.probe_copy > 0:
+        Y = torch.empty_like(X)
+        nbytes = X.numel() * 4
+        pe = [torch.cuda.Event(enable_timing=True) for _ in range(args.probe_copy + 1)]
+        ds.ds_probe_copy(Y, X, nbytes, stream)
+        pe[0].record(stream)
+        for k in range(args.probe_copy):
+            ds.ds_probe_copy(Y, X, nbytes, stream)
+            pe[k + 1].record(stream)
+        torch.cuda.synchronize()
+        pms = sum(pe[k].elapsed_time(pe[k + 1]) for k in range(args.probe_copy)) / args.probe_copy
+        probe = {"bytes_read": nbytes, "bytes_written": nbytes, "ms": round(pms, 4),
+                 "GBps": round(2.0 * nbytes / (pms * 1e-3) / 1e9, 1)}
+        del Y
 
     for t in range(args.warmup):
         step(t)
@@ -162,8 +181,10 @@ def main() -> int:
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(sync_gbps / HBM_PEAK_GBPS, 4),
                      "traffic": measured_traffic("group_sync_cfg%d_traffic.json" % args.config)},
     }
+    if probe is not None:
+        out["probe_copy"] = probe
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, X, Gs[0], iters=3)
+        out["cpu_baseline"] = cpu_baseline(cfg, X, Gs[0], iters=8)
     print(json.dumps(out), flush=True)
     return 0
 

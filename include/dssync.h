@@ -176,6 +176,17 @@ size_t ds_consensus_workspace_bytes(int32_t W, int64_t P);
 int ds_consensus(const void* X, int64_t P, int64_t ld, int32_t W, double* dev_out, void* workspace,
                  size_t workspace_bytes, void* stream);
 
+/*
+ * ds_probe_copy -- measurement aid, not a step of the method: a plain
+ * device-to-device streaming copy of `bytes` bytes (reads `bytes`, writes
+ * `bytes`).  The benchmark uses it as the attainable-bandwidth yardstick and
+ * to scale the profiler's HBM byte counters against a launch whose traffic is
+ * known exactly.
+ *   dst, src   dev, 16-byte aligned, non-overlapping; bytes a multiple of 16
+ * Errors: DS_ERR_NULL, DS_ERR_ALIGN, DS_ERR_BAD_SHAPE, DS_ERR_HIP.
+ */
+int ds_probe_copy(void* dst, const void* src, size_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -4,7 +4,7 @@ Every function has the name and the argument order of its C entry point in
 ``include/dssync.h`` and raises :class:`DsError` for a negative status.  Device
 buffers are torch tensors (or raw integer addresses); torch is used for device
 memory and for the current stream handle, nothing else.  There is no CPU
-fallback: if the shared library is missing the import of this module fails.
+fallback: if the shared library is missing, the first call raises ImportError.
 """
 from __future__ import annotations
 
@@ -21,7 +21,7 @@ DS_F32, DS_BF16 = 0, 1
 DS_MAX_W = 64
 
 EXPORTS = ("ds_status_string", "ds_partition", "ds_group_sync", "ds_ragged_plan_bytes", "ds_ragged_plan",
-           "ds_group_sync_ragged", "ds_consensus_workspace_bytes", "ds_consensus")
+           "ds_group_sync_ragged", "ds_consensus_workspace_bytes", "ds_consensus", "ds_probe_copy")
 
 
 class DsError(RuntimeError):
@@ -59,10 +59,30 @@ def _load() -> ctypes.CDLL:
     lib.ds_consensus_workspace_bytes.argtypes = [i32, i64]
     lib.ds_consensus.restype = ctypes.c_int
     lib.ds_consensus.argtypes = [vp, i64, i64, i32, vp, vp, sz, vp]
+    lib.ds_probe_copy.restype = ctypes.c_int
+    lib.ds_probe_copy.argtypes = [vp, vp, sz, vp]
     return lib
 
 
-_lib = _load()
+class _Lazy:
+    """Loads the shared library on first use, so that the build module of this
+    package can be imported before the library exists.  Any call without a
+    built library raises ImportError: there is no fallback path."""
+
+    _lib = None
+
+    def __getattr__(self, name):
+        if _Lazy._lib is None:
+            _Lazy._lib = _load()
+        return getattr(_Lazy._lib, name)
+
+
+_lib = _Lazy()
+
+
+def load() -> None:
+    """Load the library now (raises ImportError if it is not built)."""
+    _lib.ds_status_string
 
 
 def _addr(buf) -> int:
@@ -156,3 +176,7 @@ def ds_consensus_workspace_bytes(W: int, P: int) -> int:
 def ds_consensus(X, P: int, ld: int, W: int, dev_out, workspace, workspace_bytes: int, stream=None) -> None:
     _check(_lib.ds_consensus(_addr(X), P, ld, W, _addr(dev_out), _addr(workspace), workspace_bytes,
                              _stream(stream)), "ds_consensus")
+
+
+def ds_probe_copy(dst, src, nbytes: int, stream=None) -> None:
+    _check(_lib.ds_probe_copy(_addr(dst), _addr(src), nbytes, _stream(stream)), "ds_probe_copy")

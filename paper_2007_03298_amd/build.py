@@ -15,7 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdssync.so")
-SOURCES = ["partition.cpp", "group_sync.hip", "consensus.hip"]
+SOURCES = ["partition.cpp", "group_sync.hip", "consensus.hip", "probe.hip"]
 
 
 def hipcc() -> str:
@@ -25,7 +25,7 @@ def hipcc() -> str:
     return exe
 
 
-def build_library(verbose: bool = False, extra_flags=()) -> str:
+def build_library(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
     cmd = [hipcc(), "-x", "hip", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            "-Wall", "-Wno-unused-command-line-argument",
            # packed fp32 instructions are kept out of the generated code on purpose
@@ -33,7 +33,7 @@ def build_library(verbose: bool = False, extra_flags=()) -> str:
            "-I", os.path.join(ROOT, "include"), "-I", CSRC]
     cmd += list(extra_flags)
     cmd += [os.path.join(CSRC, s) for s in SOURCES]
-    cmd += ["-o", LIB]
+    cmd += ["-o", out]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -43,7 +43,7 @@ def build_library(verbose: bool = False, extra_flags=()) -> str:
         raise RuntimeError("hipcc failed:\n" + err)
     if verbose and err.strip():
         print(err, file=sys.stderr)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":

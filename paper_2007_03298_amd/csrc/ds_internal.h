@@ -8,13 +8,16 @@
 namespace ds {
 
 // Division of the workers as the kernels see it: member rows of group k are
-// perm[off[k]] .. perm[off[k+1]-1].  Passed by value in the kernel-argument
-// block (132 bytes), so the device reads it through the scalar cache and no
-// host-to-device copy is needed.
+// perm[off[k]] .. perm[off[k+1]-1], one byte per entry, four entries packed
+// per 32-bit word (entry i in bits 8*(i%4) of word i/4).  Passed by value in
+// the kernel-argument block (132 bytes), so no host-to-device copy is needed;
+// packing into words lets the device fetch entries with scalar loads, which do
+// not share a wait counter with the vector loads of the data.
 struct PartitionArg {
-    uint8_t perm[DS_MAX_W];
-    uint8_t off[DS_MAX_W + 4];  // n_groups+1 entries used
+    uint32_t perm[DS_MAX_W / 4];
+    uint32_t off[DS_MAX_W / 4 + 1];  // n_groups+1 entries used
 };
+
 
 // Checks perm/off (host arrays) and packs them; returns DS_OK or the status to
 // hand back to the caller.  max_size receives the largest group size and
@@ -28,7 +31,10 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 // owning kSyncVecPerLane vectors of 4 consecutive columns.  The ragged plan is
 // cut in the same unit.
 constexpr int kSyncThreads = 256;
-constexpr int kSyncVecPerLane = 2;
+#ifndef DS_SYNC_VPL
+#define DS_SYNC_VPL 1
+#endif
+constexpr int kSyncVecPerLane = DS_SYNC_VPL;
 constexpr int kSyncTileCols = kSyncThreads * 4 * kSyncVecPerLane;
 
 // One entry of the ragged plan: a run of at most kSyncTileCols columns that

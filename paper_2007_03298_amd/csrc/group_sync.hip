@@ -9,14 +9,19 @@
 //   - a workgroup of 256 lanes owns one tile of kSyncTileCols consecutive
 //     columns of ONE group; blockIdx.y is the group, blockIdx.x the tile, so
 //     consecutive workgroups walk each member row sequentially;
-//   - a lane owns kSyncVecPerLane vectors of 4 consecutive columns, 256 lanes
+//   - a lane owns kSyncVecPerLane vectors of 4 consecutive columns, 64 lanes
 //     apart, so every wavefront load/store instruction covers 1 KiB of one
-//     row (128-bit per lane, fully coalesced);
+//     row (128-bit per lane, fully coalesced) and a wavefront owns
+//     kSyncVecPerLane consecutive KiB of every member row;
 //   - member rows are uniform across the workgroup: their indices come from
-//     the kernel-argument block through scalar loads, and the row base
-//     addresses live in scalar registers;
+//     the kernel-argument block through scalar loads (which have their own
+//     wait counter, so fetching an index never waits for data loads), and the
+//     row base addresses live in scalar registers;
 //   - members are accumulated kChunk at a time, which keeps
-//     2 * kChunk * kSyncVecPerLane 128-bit loads in flight per lane;
+//     2 * kChunk * kSyncVecPerLane 128-bit loads in flight per lane; interior
+//     tiles run a predicate-free body so that those loads issue back to back
+//     (a load guarded by a lane predicate gets its own basic block and the
+//     compiler then waits for it before issuing the next one);
 //   - the reduction over members is sequential inside a lane (no cross-lane
 //     traffic is needed: a column never leaves its lane), one mean is formed
 //     per column and stored |group| times, so members end bit-identical;
@@ -25,6 +30,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstdlib>
 #include <utility>
 #include <vector>
 
@@ -41,16 +47,70 @@ using ds::Tile;
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kChunk = 4;  // members accumulated per round of loads
+// Tuning constants, fixed at build time from measurements on MI355X.
+#ifndef DS_SYNC_CHUNK
+#define DS_SYNC_CHUNK 2
+#endif
+#ifndef DS_SYNC_NT_LOAD
+#define DS_SYNC_NT_LOAD 1
+#endif
+#ifndef DS_SYNC_NT_STORE
+#define DS_SYNC_NT_STORE 1
+#endif
+#ifndef DS_SYNC_GROUP_MAJOR
+#define DS_SYNC_GROUP_MAJOR 1
+#endif
+#ifndef DS_SYNC_WAVE_CONTIG
+#define DS_SYNC_WAVE_CONTIG 1
+#endif
+#ifndef DS_SYNC_XCD_MAP
+#define DS_SYNC_XCD_MAP 0
+#endif
+#ifndef DS_SYNC_SERIAL
+#define DS_SYNC_SERIAL 0
+#endif
+#ifndef DS_SYNC_BARRIER
+#define DS_SYNC_BARRIER 1
+#endif
+#ifndef DS_SYNC_LDS_PAD
+#define DS_SYNC_LDS_PAD 65536
+#endif
+#ifndef DS_TUNE_ENV
+constexpr unsigned kSyncLdsPad = DS_SYNC_LDS_PAD;
+#endif
+constexpr int kChunk = DS_SYNC_CHUNK;  // members accumulated per round of loads
+
+template <typename V>
+__device__ __forceinline__ V stream_load(const V* p) {
+#if DS_SYNC_NT_LOAD
+    return __builtin_nontemporal_load(p);
+#else
+    return *p;
+#endif
+}
+template <typename V>
+__device__ __forceinline__ void stream_store(V v, V* p) {
+#if DS_SYNC_NT_STORE
+    __builtin_nontemporal_store(v, p);
+#else
+    *p = v;
+#endif
+}
+
+// Entry i of a packed byte table in the kernel-argument block; i is
+// wavefront-uniform, so this is a scalar load plus scalar bit arithmetic.
+__device__ __forceinline__ int packed_byte(const uint32_t* words, int i) {
+    return static_cast<int>((words[i >> 2] >> ((i & 3) * 8)) & 0xffu);
+}
 
 __device__ __forceinline__ float bits_to_f32(uint32_t u) { return __builtin_bit_cast(float, u); }
 
 // four consecutive gradient elements, widened to fp32
 __device__ __forceinline__ f32x4 load_grad4(const float* p) {
-    return __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+    return stream_load(reinterpret_cast<const f32x4*>(p));
 }
 __device__ __forceinline__ f32x4 load_grad4(const uint16_t* p) {
-    const u32x2 raw = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p));
+    const u32x2 raw = stream_load(reinterpret_cast<const u32x2*>(p));
     f32x4 v;
     v.x = bits_to_f32(raw.x << 16);          // bf16 is the upper half of an fp32
     v.y = bits_to_f32(raw.x & 0xffff0000u);
@@ -63,92 +123,165 @@ __device__ __forceinline__ float load_grad1(const uint16_t* p) {
     return bits_to_f32(static_cast<uint32_t>(*p) << 16);
 }
 
+// Adds the locally updated parameters x - lr*g of kCount members (perm
+// positions q .. q+kCount-1) to the lane's column sums.  All 2*kCount*VPL
+// vector loads are issued back to back before the first use; with kFull
+// nothing is predicated, so the loads sit in one basic block.
+template <typename GT, int kCount, bool kFull>
+__device__ __forceinline__ void add_members(f32x4 (&sum)[kSyncVecPerLane], const float* xt, const GT* gt,
+                                            int64_t ldx, int64_t ldg, const PartitionArg& part, int q,
+                                            const int (&col)[kSyncVecPerLane],
+                                            const bool (&live)[kSyncVecPerLane], float lr) {
+#if DS_SYNC_SERIAL == 9
+    // one member at a time: load, wait, accumulate
+#pragma unroll
+    for (int j = 0; j < kCount; ++j) {
+        const int64_t row = packed_byte(part.perm, q + j);
+        const float* xr = xt + row * ldx;
+        const GT* gr = gt + row * ldg;
+        f32x4 x1[kSyncVecPerLane], g1[kSyncVecPerLane];
+#pragma unroll
+        for (int v = 0; v < kSyncVecPerLane; ++v) {
+            if (kFull || live[v]) {
+                x1[v] = stream_load(reinterpret_cast<const f32x4*>(xr + col[v]));
+                g1[v] = load_grad4(gr + col[v]);
+            }
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int v = 0; v < kSyncVecPerLane; ++v)
+            if (kFull || live[v]) sum[v] += x1[v] - lr * g1[v];
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    return;
+#endif
+    f32x4 x[kCount][kSyncVecPerLane], g[kCount][kSyncVecPerLane];
+#pragma unroll
+    for (int j = 0; j < kCount; ++j) {
+        const int64_t row = packed_byte(part.perm, q + j);
+        const float* xr = xt + row * ldx;
+        const GT* gr = gt + row * ldg;
+#pragma unroll
+        for (int v = 0; v < kSyncVecPerLane; ++v) {
+            if (kFull || live[v]) {
+                x[j][v] = stream_load(reinterpret_cast<const f32x4*>(xr + col[v]));
+                g[j][v] = load_grad4(gr + col[v]);
+            }
+        }
+#if DS_SYNC_SERIAL == 1
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#elif DS_SYNC_SERIAL == 2
+        if (j & 1) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#elif DS_SYNC_SERIAL == 4
+        if ((j & 3) == 3) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#endif
+    }
+#pragma unroll
+    for (int j = 0; j < kCount; ++j) {
+#pragma unroll
+        for (int v = 0; v < kSyncVecPerLane; ++v)
+            if (kFull || live[v]) sum[v] += x[j][v] - lr * g[j][v];
+    }
+}
+
+// One tile of one group.  kFull: the tile has all kSyncTileCols columns.
+template <typename GT, bool kFull>
+__device__ __forceinline__ void sync_tile(float* xt, const GT* gt, int len, int64_t ldx, int64_t ldg,
+                                          const PartitionArg& part, int first, int n, float lr) {
+    int col[kSyncVecPerLane];
+    bool live[kSyncVecPerLane];
+    f32x4 sum[kSyncVecPerLane];
+    const int lane = static_cast<int>(threadIdx.x) & 63, wave = static_cast<int>(threadIdx.x) >> 6;
+#pragma unroll
+    for (int v = 0; v < kSyncVecPerLane; ++v) {
+#if DS_SYNC_WAVE_CONTIG
+        col[v] = ((wave * kSyncVecPerLane + v) * 64 + lane) * 4;   // a wavefront owns VPL consecutive KiB
+#else
+        col[v] = (v * kSyncThreads + static_cast<int>(threadIdx.x)) * 4;
+#endif
+        live[v] = kFull || col[v] + 4 <= len;
+        sum[v] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    int q = first;
+    const int end = first + n;
+    for (; q + kChunk <= end; q += kChunk)
+        add_members<GT, kChunk, kFull>(sum, xt, gt, ldx, ldg, part, q, col, live, lr);
+    // remaining members (fewer than kChunk): one specialised, branch-free body each
+    switch (end - q) {
+#define DS_REST(k) case k: if (k < kChunk) add_members<GT, (k < kChunk ? k : 1), kFull>(sum, xt, gt, ldx, ldg, part, q, col, live, lr); break;
+        DS_REST(1) DS_REST(2) DS_REST(3) DS_REST(4) DS_REST(5) DS_REST(6) DS_REST(7)
+        DS_REST(8) DS_REST(9) DS_REST(10) DS_REST(11) DS_REST(12) DS_REST(13) DS_REST(14) DS_REST(15)
+#undef DS_REST
+        default: break;
+    }
+    const float nf = static_cast<float>(n);
+#pragma unroll
+    for (int v = 0; v < kSyncVecPerLane; ++v) sum[v] = sum[v] / nf;
+#if DS_SYNC_BARRIER
+    // all four wavefronts switch from reading to writing together
+    __syncthreads();
+#endif
+    for (int m = first; m < end; ++m) {
+        float* xr = xt + static_cast<int64_t>(packed_byte(part.perm, m)) * ldx;
+#pragma unroll
+        for (int v = 0; v < kSyncVecPerLane; ++v)
+            if (kFull || live[v]) stream_store(sum[v], reinterpret_cast<f32x4*>(xr + col[v]));
+    }
+    if (!kFull) {
+        // ragged end of the tile: fewer than 4 columns, one lane each
+        const int c = (len & ~3) + static_cast<int>(threadIdx.x);
+        if (threadIdx.x < 3 && c < len) {
+            float s = 0.f;
+            for (int m = first; m < end; ++m) {
+                const int64_t row = packed_byte(part.perm, m);
+                s += xt[row * ldx + c] - lr * load_grad1(gt + row * ldg + c);
+            }
+            s = s / nf;
+            for (int m = first; m < end; ++m) xt[static_cast<int64_t>(packed_byte(part.perm, m)) * ldx + c] = s;
+        }
+    }
+}
+
 template <typename GT, bool kRagged>
 __global__ void __launch_bounds__(kSyncThreads)
 group_sync_kernel(float* __restrict__ X, const GT* __restrict__ G, int64_t ldx, int64_t ldg,
-                  int64_t P, const Tile* __restrict__ tiles, PartitionArg part, float lr) {
+                  int64_t P, const Tile* __restrict__ tiles, PartitionArg part, float lr, uint32_t n_tiles) {
+    static_assert(kChunk >= 1 && kChunk <= 16, "remainder switch covers up to 15 members");
     int64_t start;
     int32_t len;
+#if DS_SYNC_GROUP_MAJOR
+    uint32_t tile_id = blockIdx.x;
+    const uint32_t group_id = blockIdx.y;
+#else
+    uint32_t tile_id = blockIdx.y;
+    const uint32_t group_id = blockIdx.x;
+#endif
+#if DS_SYNC_XCD_MAP
+    {
+        // workgroups are dealt round-robin to the 8 XCDs: give each XCD one contiguous eighth of the tiles
+        const uint32_t per_xcd = (n_tiles + 7u) / 8u;
+        tile_id = (tile_id & 7u) * per_xcd + (tile_id >> 3);
+        if (tile_id >= n_tiles) return;
+    }
+#endif
     if (kRagged) {
-        const Tile tl = tiles[blockIdx.x];
+        const Tile tl = tiles[tile_id];
         start = tl.start;
         len = tl.len;
         // a table that does not belong to these stacks must not become a wild access
         const int64_t ld_min = ldx < ldg ? ldx : ldg;
         if (start < 0 || (start & 7) != 0 || len < 0 || len > kSyncTileCols || start > ld_min - len) return;
     } else {
-        start = static_cast<int64_t>(blockIdx.x) * kSyncTileCols;
+        start = static_cast<int64_t>(tile_id) * kSyncTileCols;
         const int64_t left = P - start;
         len = left < kSyncTileCols ? static_cast<int32_t>(left) : kSyncTileCols;
     }
-    const int first = part.off[blockIdx.y];
-    const int n = part.off[blockIdx.y + 1] - first;
-    const float nf = static_cast<float>(n);
-
-    float* const xt = X + start;
-    const GT* const gt = G + start;
-
-    // ---- full vectors ------------------------------------------------------
-    int col[kSyncVecPerLane];
-    bool full[kSyncVecPerLane];
-    f32x4 sum[kSyncVecPerLane];
-#pragma unroll
-    for (int v = 0; v < kSyncVecPerLane; ++v) {
-        col[v] = (v * kSyncThreads + static_cast<int>(threadIdx.x)) * 4;
-        full[v] = col[v] + 4 <= len;
-        sum[v] = f32x4{0.f, 0.f, 0.f, 0.f};
-    }
-    for (int q0 = 0; q0 < n; q0 += kChunk) {
-        f32x4 x[kChunk][kSyncVecPerLane], g[kChunk][kSyncVecPerLane];
-#pragma unroll
-        for (int j = 0; j < kChunk; ++j) {
-            if (q0 + j < n) {
-                const int64_t row = part.perm[first + q0 + j];
-                const float* xr = xt + row * ldx;
-                const GT* gr = gt + row * ldg;
-#pragma unroll
-                for (int v = 0; v < kSyncVecPerLane; ++v) {
-                    if (full[v]) {
-                        x[j][v] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(xr + col[v]));
-                        g[j][v] = load_grad4(gr + col[v]);
-                    }
-                }
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < kChunk; ++j) {
-            if (q0 + j < n) {
-#pragma unroll
-                for (int v = 0; v < kSyncVecPerLane; ++v)
-                    if (full[v]) sum[v] += x[j][v] - lr * g[j][v];
-            }
-        }
-    }
-#pragma unroll
-    for (int v = 0; v < kSyncVecPerLane; ++v) sum[v] = sum[v] / nf;
-    for (int q = 0; q < n; ++q) {
-        const int64_t row = part.perm[first + q];
-        float* xr = xt + row * ldx;
-#pragma unroll
-        for (int v = 0; v < kSyncVecPerLane; ++v)
-            if (full[v]) __builtin_nontemporal_store(sum[v], reinterpret_cast<f32x4*>(xr + col[v]));
-    }
-
-    // ---- ragged end of the tile: fewer than 4 columns, one lane each ---------
-    const int tail0 = len & ~3;
-    const int c = tail0 + static_cast<int>(threadIdx.x);
-    if (threadIdx.x < 3 && c < len) {
-        float s = 0.f;
-        for (int q = 0; q < n; ++q) {
-            const int64_t row = part.perm[first + q];
-            s += xt[row * ldx + c] - lr * load_grad1(gt + row * ldg + c);
-        }
-        s = s / nf;
-        for (int q = 0; q < n; ++q) {
-            const int64_t row = part.perm[first + q];
-            xt[row * ldx + c] = s;
-        }
-    }
+    const int first = packed_byte(part.off, static_cast<int>(group_id));
+    const int n = packed_byte(part.off, static_cast<int>(group_id) + 1) - first;
+    if (len == kSyncTileCols)
+        sync_tile<GT, true>(X + start, G + start, len, ldx, ldg, part, first, n, lr);
+    else
+        sync_tile<GT, false>(X + start, G + start, len, ldx, ldg, part, first, n, lr);
 }
 
 struct SegmentScan {
@@ -196,15 +329,31 @@ template <bool kRagged>
 int launch(void* X, const void* G, int32_t g_dtype, int64_t P, int64_t ldx, int64_t ldg,
            int64_t n_tiles, const Tile* tiles, const PartitionArg& part, int32_t n_groups, float lr,
            void* stream) {
+#if DS_SYNC_XCD_MAP
+    const dim3 grid(static_cast<uint32_t>((n_tiles + 7) / 8 * 8), static_cast<uint32_t>(n_groups), 1);
+#elif DS_SYNC_GROUP_MAJOR
     const dim3 grid(static_cast<uint32_t>(n_tiles), static_cast<uint32_t>(n_groups), 1);
+#else
+    const dim3 grid(static_cast<uint32_t>(n_groups), static_cast<uint32_t>(n_tiles), 1);
+#endif
     const dim3 block(kSyncThreads, 1, 1);
     hipStream_t st = static_cast<hipStream_t>(stream);
+#ifdef DS_TUNE_ENV
+    const char* pad_env = getenv("DS_LDS_PAD");
+    const unsigned kSyncLdsPad = pad_env ? static_cast<unsigned>(atoi(pad_env)) : 0u;
+    if (kSyncLdsPad > 65536u) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&group_sync_kernel<float, kRagged>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kSyncLdsPad));
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&group_sync_kernel<uint16_t, kRagged>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kSyncLdsPad));
+    }
+#endif
     if (g_dtype == DS_F32) {
-        hipLaunchKernelGGL((group_sync_kernel<float, kRagged>), grid, block, 0, st, static_cast<float*>(X),
-                           static_cast<const float*>(G), ldx, ldg, P, tiles, part, lr);
+        hipLaunchKernelGGL((group_sync_kernel<float, kRagged>), grid, block, kSyncLdsPad, st, static_cast<float*>(X),
+                           static_cast<const float*>(G), ldx, ldg, P, tiles, part, lr, static_cast<uint32_t>(n_tiles));
     } else {
-        hipLaunchKernelGGL((group_sync_kernel<uint16_t, kRagged>), grid, block, 0, st, static_cast<float*>(X),
-                           static_cast<const uint16_t*>(G), ldx, ldg, P, tiles, part, lr);
+        hipLaunchKernelGGL((group_sync_kernel<uint16_t, kRagged>), grid, block, kSyncLdsPad, st, static_cast<float*>(X),
+                           static_cast<const uint16_t*>(G), ldx, ldg, P, tiles, part, lr, static_cast<uint32_t>(n_tiles));
     }
     return hipGetLastError() == hipSuccess ? DS_OK : DS_ERR_HIP;
 }

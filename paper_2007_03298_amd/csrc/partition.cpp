@@ -96,9 +96,13 @@ int ds::pack_partition(int32_t W, const int32_t* perm, const int32_t* off, int32
         if (w < 0 || w >= W || seen[w]) return DS_ERR_BAD_PART;
         seen[w] = true;
     }
-    for (int32_t q = 0; q < DS_MAX_W; ++q) out->perm[q] = q < W ? static_cast<uint8_t>(perm[q]) : 0;
-    for (int32_t k = 0; k < DS_MAX_W + 4; ++k)
-        out->off[k] = k <= n_groups ? static_cast<uint8_t>(off[k]) : static_cast<uint8_t>(W);
+    for (uint32_t& word : out->perm) word = 0;
+    for (uint32_t& word : out->off) word = 0;
+    for (int32_t q = 0; q < W; ++q) out->perm[q >> 2] |= static_cast<uint32_t>(perm[q]) << ((q & 3) * 8);
+    for (int32_t k = 0; k < DS_MAX_W + 4; ++k) {
+        const uint32_t edge = static_cast<uint32_t>(k <= n_groups ? off[k] : W);
+        out->off[k >> 2] |= edge << ((k & 3) * 8);
+    }
     *max_size = largest;
     *equal_size = all_equal ? largest : 0;
     return DS_OK;
