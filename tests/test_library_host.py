@@ -135,7 +135,13 @@ def test_ragged_plan_bytes_and_plan_errors():
     assert ds.ds_ragged_plan_bytes([(0, 0)]) == 0
     one = ds.ds_ragged_plan_bytes([(0, 1)])
     assert one == 16
-    assert ds.ds_ragged_plan_bytes([(0, 2048), (2048, 2049), (8192, 5)]) == 16 * (1 + 2 + 1)
+    # one 16-byte entry per tile; the tile width is the library's business, but the
+    # count is additive over segments and grows with the length
+    a, b, c = (0, 100000), (100096, 7), (200000, 12345)
+    assert ds.ds_ragged_plan_bytes([a, b, c]) == sum(ds.ds_ragged_plan_bytes([x]) for x in (a, b, c))
+    assert ds.ds_ragged_plan_bytes([b]) == 16
+    assert ds.ds_ragged_plan_bytes([a]) > ds.ds_ragged_plan_bytes([c]) > 16
+    assert ds.ds_ragged_plan_bytes([a]) % 16 == 0
     assert ds.ds_ragged_plan_bytes([(3, 5)]) == 0   # invalid list
     with pytest.raises(ds.DsError) as e:
         ds.ds_ragged_plan([(0, 64), (32, 64)], 4096, 4096, A, 1 << 20, stream=0)   # overlap
