@@ -44,9 +44,9 @@ def cpu_baseline(cfg, X, G, iters: int):
     """The oracle, as it stands, on the host cores: whole configuration-3 stacks."""
     import numpy as np
     import oracle
-    Xh = X.cpu().numpy()
-    Gh = G.cpu().numpy()
-    W, P = Xh.shape
+    W, P = cfg.W, cfg.P
+    Xh = np.ascontiguousarray(X[:, :P].cpu().numpy())
+    Gh = np.ascontiguousarray(G[:, :P].cpu().numpy())
     t_step = t_cons = 0.0
     for t in range(iters):
         a = time.perf_counter()
@@ -78,6 +78,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=3, help="benchmark configuration (flat fp32 ones: 1-4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--dense-rows", action="store_true",
+                    help="leading dimension = P (rows not 256-byte aligned) instead of P rounded up to 64")
     ap.add_argument("--probe-copy", type=int, default=0, metavar="N",
                     help="also launch the plain copy kernel N times on a stack-sized buffer before the "
                          "timed region (yardstick for bandwidth and for profiler counter scaling)")
@@ -100,7 +102,8 @@ def main() -> int:
         print("bench.py: --config must be one of the flat configurations 1-4", file=sys.stderr)
         return 2
     W, P = cfg.W, cfg.P
-    run = wl.Run(cfg, dev)
+    ld = P if args.dense_rows else wl.padded_ld(P)   # rows start on 256-byte boundaries
+    run = wl.Run(cfg, dev, P=P, ld=ld)
     X = run.init_params()
     n_grad = 2                                   # gradient stacks resident in HBM, used in turn
     Gs = [run.gradients() for _ in range(n_grad)]
@@ -113,10 +116,10 @@ def main() -> int:
         perm, off = ds.ds_partition(cfg.seed, t, W, cfg.sizes)
         if ev:
             ev[0].record(stream)
-        ds.ds_group_sync(X, Gs[t % n_grad], ds.DS_F32, P, P, P, W, perm, off, cfg.lr, stream)
+        ds.ds_group_sync(X, Gs[t % n_grad], ds.DS_F32, P, ld, ld, W, perm, off, cfg.lr, stream)
         if ev:
             ev[1].record(stream)
-        ds.ds_consensus(X, P, P, W, dev_out, ws, ws_bytes, stream)
+        ds.ds_consensus(X, P, ld, W, dev_out, ws, ws_bytes, stream)
         if ev:
             ev[2].record(stream)
 
@@ -169,7 +172,7 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": cfg.name, "W": W, "group_size": cfg.group, "P": P, "lr": cfg.lr,
+        "config": {"workload": cfg.name, "W": W, "group_size": cfg.group, "P": P, "ld": ld, "lr": cfg.lr,
                    "seed": cfg.seed, "bytes_per_step": int(sync_bytes + cons_bytes)},
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "group_sync": {"ms": round(sync_ms, 4), "GBps": round(sync_gbps, 1),

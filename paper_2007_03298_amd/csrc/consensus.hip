@@ -11,7 +11,7 @@
 //     error is relative to the difference itself (and exactly zero for
 //     identical replicas); it is squared and summed into one fp32 accumulator
 //     per worker per lane;
-//   - workgroups walk the column tiles with a grid stride; at the end the lane
+//   - a workgroup walks a run of consecutive column tiles; at the end the lane
 //     accumulators are widened to fp64, reduced across the wavefront with
 //     lane shuffles, across the 4 wavefronts through LDS, and written as one
 //     partial row per workgroup;
@@ -25,7 +25,7 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
-constexpr int kMaxBlocks = 2048;  // upper bound of the grid of the partial kernel
+constexpr int kMaxBlocks = 8192;  // upper bound of the grid of the partial kernel
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
@@ -36,69 +36,100 @@ template <> struct VecOf<2> { typedef f32x2 type; };
 
 __host__ __device__ constexpr int padded_w(int W) { return W <= 8 ? 8 : W <= 16 ? 16 : W <= 32 ? 32 : 64; }
 
+#ifndef DS_CONS_LDS_PAD
+#define DS_CONS_LDS_PAD 0
+#endif
+#ifdef DS_TUNE_ENV
+#include <cstdlib>
+#undef DS_CONS_LDS_PAD
+#define DS_CONS_LDS_PAD (getenv("DS_CONS_LDS") ? atoi(getenv("DS_CONS_LDS")) : 0)
+#undef DS_CONS_TARGET_BLOCKS
+#define DS_CONS_TARGET_BLOCKS (getenv("DS_CONS_BLOCKS") ? atoi(getenv("DS_CONS_BLOCKS")) : 4096)
+#endif
+#ifndef DS_CONS_TARGET_BLOCKS
+#define DS_CONS_TARGET_BLOCKS 4096
+#endif
+
+// Adds one tile's squared deviations to the lane accumulators.  kFull: every
+// lane's kVec columns lie inside the row (no predicates, so the W loads issue
+// back to back).
+template <int kWPad, int kVec, bool kFull>
+__device__ __forceinline__ void consensus_tile(float (&acc)[kWPad], const float* __restrict__ X, int64_t c,
+                                               int64_t P, int64_t ld, int W) {
+    typedef typename VecOf<kVec>::type vec_t;
+    vec_t row[kWPad];
+#pragma unroll
+    for (int i = 0; i < kWPad; ++i) {
+        if (i < W) {
+            if (kFull) {
+                row[i] = __builtin_nontemporal_load(reinterpret_cast<const vec_t*>(X + i * ld + c));
+            } else {
+                // last, partial vector of the row: columns at or beyond P count as 0
+                // in every row, which adds nothing to any deviation
+#pragma unroll
+                for (int e = 0; e < kVec; ++e) row[i][e] = (c + e < P) ? X[i * ld + c + e] : 0.f;
+            }
+        }
+    }
+    double mean[kVec];
+#pragma unroll
+    for (int e = 0; e < kVec; ++e) mean[e] = 0.0;
+#pragma unroll
+    for (int i = 0; i < kWPad; ++i) {
+        if (i < W) {
+#pragma unroll
+            for (int e = 0; e < kVec; ++e) mean[e] += static_cast<double>(row[i][e]);
+        }
+    }
+    // mean as an unevaluated fp32 pair hi + lo (|lo| <= ulp(hi)/2): subtracting
+    // hi, then lo, in fp32 leaves an error that is relative to the difference
+    // itself, and is exactly 0 when every row equals the mean
+    const double wd = static_cast<double>(W);
+    float hi[kVec], lo[kVec];
+#pragma unroll
+    for (int e = 0; e < kVec; ++e) {
+        const double m = mean[e] / wd;
+        hi[e] = static_cast<float>(m);
+        lo[e] = static_cast<float>(m - static_cast<double>(hi[e]));
+    }
+#pragma unroll
+    for (int i = 0; i < kWPad; ++i) {
+        if (i < W) {
+#pragma unroll
+            for (int e = 0; e < kVec; ++e) {
+                const float d = (row[i][e] - hi[e]) - lo[e];
+                acc[i] = __builtin_fmaf(d, d, acc[i]);
+            }
+        }
+    }
+}
+
 template <int kWPad, int kVec>
 __global__ void __launch_bounds__(kThreads)
-consensus_partial_kernel(const float* __restrict__ X, int64_t P, int64_t ld, int W,
+consensus_partial_kernel(const float* __restrict__ X, int64_t P, int64_t ld, int W, int tiles_per_block,
                          double* __restrict__ partial) {
-    typedef typename VecOf<kVec>::type vec_t;
     constexpr int kTileCols = kThreads * kVec;
     float acc[kWPad];
 #pragma unroll
     for (int i = 0; i < kWPad; ++i) acc[i] = 0.f;
 
+    // a workgroup owns tiles_per_block consecutive tiles
     const int64_t n_tiles = (P + kTileCols - 1) / kTileCols;
-    const double wd = static_cast<double>(W);
-    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    const int64_t tile0 = static_cast<int64_t>(blockIdx.x) * tiles_per_block;
+    const int64_t tile1 = tile0 + tiles_per_block < n_tiles ? tile0 + tiles_per_block : n_tiles;
+    for (int64_t tile = tile0; tile < tile1; ++tile) {
         const int64_t c = tile * kTileCols + static_cast<int64_t>(threadIdx.x) * kVec;
-        vec_t row[kWPad];
-        if (c + kVec <= P) {
-#pragma unroll
-            for (int i = 0; i < kWPad; ++i)
-                if (i < W) row[i] = *reinterpret_cast<const vec_t*>(X + i * ld + c);
-        } else {
-            // last, partial vector of the row: columns at or beyond P count as 0 in
-            // every row, which adds nothing to any deviation
-#pragma unroll
-            for (int i = 0; i < kWPad; ++i) {
-                if (i < W) {
-#pragma unroll
-                    for (int e = 0; e < kVec; ++e) row[i][e] = (c + e < P) ? X[i * ld + c + e] : 0.f;
-                }
-            }
-        }
-        double mean[kVec];
-#pragma unroll
-        for (int e = 0; e < kVec; ++e) mean[e] = 0.0;
-#pragma unroll
-        for (int i = 0; i < kWPad; ++i) {
-            if (i < W) {
-#pragma unroll
-                for (int e = 0; e < kVec; ++e) mean[e] += static_cast<double>(row[i][e]);
-            }
-        }
-        // mean as an unevaluated fp32 pair hi + lo (|lo| <= ulp(hi)/2): subtracting
-        // hi, then lo, in fp32 leaves an error that is relative to the difference
-        // itself, and is exactly 0 when every row equals the mean
-        float hi[kVec], lo[kVec];
-#pragma unroll
-        for (int e = 0; e < kVec; ++e) {
-            const double m = mean[e] / wd;
-            hi[e] = static_cast<float>(m);
-            lo[e] = static_cast<float>(m - static_cast<double>(hi[e]));
-        }
-#pragma unroll
-        for (int i = 0; i < kWPad; ++i) {
-            if (i < W) {
-#pragma unroll
-                for (int e = 0; e < kVec; ++e) {
-                    const float d = (row[i][e] - hi[e]) - lo[e];
-                    acc[i] = __builtin_fmaf(d, d, acc[i]);
-                }
-            }
+        if ((tile + 1) * kTileCols <= P) {
+            consensus_tile<kWPad, kVec, true>(acc, X, c, P, ld, W);
+        } else if (c < P) {
+            if (c + kVec <= P)
+                consensus_tile<kWPad, kVec, true>(acc, X, c, P, ld, W);
+            else
+                consensus_tile<kWPad, kVec, false>(acc, X, c, P, ld, W);
         }
     }
 
-    // lanes -> wavefront -> workgroup, in fp64
+    // lanes -> wavefront (fp32 butterfly) -> workgroup -> partial row (fp64)
     __shared__ double wave_sum[kWaves][kWPad];
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -154,17 +185,25 @@ extern "C" int ds_consensus(const void* X, int64_t P, int64_t ld, int32_t W, dou
     const int vec = w_pad == 64 ? 2 : 4;
     const int64_t tile_cols = static_cast<int64_t>(kThreads) * vec;
     const int64_t n_tiles = (P + tile_cols - 1) / tile_cols;
+    // consecutive tiles per workgroup: enough to amortise the end-of-block reduction,
+    // few enough to leave thousands of workgroups for the 256 CUs
+    int64_t per_block = (n_tiles + DS_CONS_TARGET_BLOCKS - 1) / DS_CONS_TARGET_BLOCKS;
+    if (per_block < 1) per_block = 1;
+    if ((n_tiles + per_block - 1) / per_block > kMaxBlocks) per_block = (n_tiles + kMaxBlocks - 1) / kMaxBlocks;
+    if (per_block > INT32_MAX) return DS_ERR_BAD_SHAPE;
     // at least one workgroup, so that P == 0 still writes a (zero) partial row
-    const int n_blocks = static_cast<int>(n_tiles < 1 ? 1 : (n_tiles < kMaxBlocks ? n_tiles : kMaxBlocks));
+    const int64_t want_blocks = (n_tiles + per_block - 1) / per_block;
+    const int n_blocks = static_cast<int>(want_blocks < 1 ? 1 : want_blocks);
+    const int tpb = static_cast<int>(per_block);
     hipStream_t st = static_cast<hipStream_t>(stream);
     const float* x = static_cast<const float*>(X);
     double* partial = static_cast<double*>(workspace);
     const dim3 grid(static_cast<uint32_t>(n_blocks)), block(kThreads);
     switch (w_pad) {
-        case 8: hipLaunchKernelGGL((consensus_partial_kernel<8, 4>), grid, block, 0, st, x, P, ld, W, partial); break;
-        case 16: hipLaunchKernelGGL((consensus_partial_kernel<16, 4>), grid, block, 0, st, x, P, ld, W, partial); break;
-        case 32: hipLaunchKernelGGL((consensus_partial_kernel<32, 4>), grid, block, 0, st, x, P, ld, W, partial); break;
-        default: hipLaunchKernelGGL((consensus_partial_kernel<64, 2>), grid, block, 0, st, x, P, ld, W, partial); break;
+        case 8: hipLaunchKernelGGL((consensus_partial_kernel<8, 4>), grid, block, DS_CONS_LDS_PAD, st, x, P, ld, W, tpb, partial); break;
+        case 16: hipLaunchKernelGGL((consensus_partial_kernel<16, 4>), grid, block, DS_CONS_LDS_PAD, st, x, P, ld, W, tpb, partial); break;
+        case 32: hipLaunchKernelGGL((consensus_partial_kernel<32, 4>), grid, block, DS_CONS_LDS_PAD, st, x, P, ld, W, tpb, partial); break;
+        default: hipLaunchKernelGGL((consensus_partial_kernel<64, 2>), grid, block, DS_CONS_LDS_PAD, st, x, P, ld, W, tpb, partial); break;
     }
     if (hipGetLastError() != hipSuccess) return DS_ERR_HIP;
     hipLaunchKernelGGL(consensus_final_kernel, dim3(static_cast<uint32_t>(W)), block, 0, st, partial, n_blocks,

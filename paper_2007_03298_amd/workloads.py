@@ -60,6 +60,13 @@ CONFIGS = {
 }
 
 
+def padded_ld(P: int, pad: int = 64) -> int:
+    """Leading dimension used by the benchmark layout: the row length rounded
+    up to ``pad`` elements, so that every row of a stack starts on a 256-byte
+    boundary (whole cache lines per wavefront access)."""
+    return (int(P) + pad - 1) // pad * pad
+
+
 def ragged_segments(seed: int = 4, n_segments: int = 199, lo: int = 256, hi: int = 4_194_304,
                     total_range: Tuple[int, int] = (99_000_000, 121_000_000),
                     pad: int = 64) -> Tuple[List[Tuple[int, int]], int, int]:

@@ -35,21 +35,23 @@ def consensus_chunk(X, c0, n, ld, W):
     return gpu_consensus(view, n, ld, W)
 
 
-def run_flat_config(idx, full_consensus):
+def run_flat_config(idx, full_consensus, dense_rows=False):
     cfg = wl.CONFIGS[idx]
     W, P = cfg.W, cfg.P
+    ld = P if dense_rows else wl.padded_ld(P)        # the benchmark's layout unless dense_rows
     free, _ = torch.cuda.mem_get_info()
-    need = 2 * W * P * 4 + (2 << 30)
+    need = 2 * W * ld * 4 + (2 << 30)
     if free < need:
         pytest.skip("needs %.1f GB of free HBM" % (need / 1e9))
     print("config", idx, cfg.name, flush=True)
-    run = wl.Run(cfg, DEV)
+    run = wl.Run(cfg, DEV, P=P, ld=ld)
     X = run.init_params()
+    pad_before = X[:, P:].clone()
     rng = np.random.default_rng(1000 + idx)
-    cols = window_columns(P, P, rng)
+    cols = window_columns(P, ld, rng)
     cols_t = torch.from_numpy(cols).to(DEV)
     Xo = X.index_select(1, cols_t).cpu().numpy()       # oracle's own state on the windows
-    G = torch.empty(W, P, dtype=torch.float32, device=DEV)
+    G = torch.empty(W, ld, dtype=torch.float32, device=DEV)
     worst_step = worst_traj = 0.0
     for t in range(cfg.T):
         run.gradients(out=G)
@@ -58,7 +60,7 @@ def run_flat_config(idx, full_consensus):
         assert perm.tolist() == po.tolist() and off.tolist() == oo.tolist()
         before = X.index_select(1, cols_t).cpu().numpy()
         Gw = G.index_select(1, cols_t).cpu().numpy()
-        ds.ds_group_sync(X, G, ds.DS_F32, P, P, P, W, perm, off, cfg.lr)
+        ds.ds_group_sync(X, G, ds.DS_F32, P, ld, ld, W, perm, off, cfg.lr)
         torch.cuda.synchronize()
         got = X.index_select(1, cols_t).cpu().numpy()
         oracle.step(before, Gw, po, oo, cfg.lr)
@@ -72,30 +74,35 @@ def run_flat_config(idx, full_consensus):
     # members identical over ALL columns, checked on the device
     for k in range(len(off) - 1):
         members = perm[off[k]:off[k + 1]]
-        ref = X[int(members[0])].view(torch.int32)
+        ref = X[int(members[0]), :P].view(torch.int32)
         for i in members[1:]:
-            assert torch.equal(ref, X[int(i)].view(torch.int32))
+            assert torch.equal(ref, X[int(i), :P].view(torch.int32))
+    assert torch.equal(X[:, P:], pad_before)                          # padding columns never written
 
     # consensus: chunks against the oracle, additivity, and (optionally) the whole stack
-    d_full = gpu_consensus(X, P, P, W)
+    d_full = gpu_consensus(X, P, ld, W)
     q = (P // 4) // 4 * 4
     edges = [0, q, 2 * q + 4, 3 * q, P]
     sq = np.zeros(W)
     for a, b in zip(edges[:-1], edges[1:]):
-        sq += consensus_chunk(X, a, b - a, P, W) ** 2
+        sq += consensus_chunk(X, a, b - a, ld, W) ** 2
     np.testing.assert_allclose(np.sqrt(sq), d_full, rtol=1e-6)
     for c0, n in [(0, 1 << 20), (edges[2], (1 << 20) + 1), (P - (1 << 20) - 4, (1 << 20) + 4)]:
-        got = consensus_chunk(X, c0, n, P, W)
+        got = consensus_chunk(X, c0, n, ld, W)
         want = oracle.consensus(np.ascontiguousarray(X[:, c0:c0 + n].cpu().numpy()))
         np.testing.assert_allclose(got, want, rtol=1e-5)
     if full_consensus:
-        want = oracle.consensus(X.cpu().numpy())
+        want = oracle.consensus(X.cpu().numpy(), P)
         np.testing.assert_allclose(d_full, want, rtol=1e-5)
     print("  consensus max %.4f" % d_full.max(), flush=True)
 
 
 def test_config2_full_size():
     run_flat_config(2, full_consensus=True)
+
+
+def test_config2_full_size_dense_rows():
+    run_flat_config(2, full_consensus=False, dense_rows=True)
 
 
 def test_config3_full_size():
