@@ -29,13 +29,17 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published
 
 
-def measured_traffic(name: str):
-    """HBM bytes per launch derived from rocprofv3 counter runs, if a summary
-    has been recorded under profiles/ (see the design doc); otherwise None."""
+def measured_traffic(name: str, workload: str):
+    """HBM bytes per launch of the dominant kernel, from the rocprofv3 counter
+    runs recorded under profiles/ (FETCH_SIZE and WRITE_SIZE, each scaled by
+    what the same counter reads for the plain copy kernel).  The counters
+    cannot be read from inside this process, so the figure is the recorded one
+    and is reported only for the workload and layout it was measured on."""
     path = os.path.join(ROOT, "profiles", name)
     try:
         with open(path) as fh:
-            return json.load(fh).get("hbm_bytes_per_launch")
+            rec = json.load(fh)
+        return rec.get("hbm_bytes_per_launch") if rec.get("workload") == workload else None
     except (OSError, ValueError):
         return None
 
@@ -182,7 +186,8 @@ def main() -> int:
                       "max_deviation": float(d.max())},
         "roofline": {"bound": "hbm", "kernel": "group_sync_kernel<float, flat>", "achieved": round(sync_gbps, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(sync_gbps / HBM_PEAK_GBPS, 4),
-                     "traffic": measured_traffic("group_sync_cfg%d_traffic.json" % args.config)},
+                     "traffic": measured_traffic("group_sync_cfg%d_traffic.txt" % args.config,
+                                                 "cfg%d W=%d g=%d P=%d ld=%d" % (args.config, W, cfg.group, P, ld))},
     }
     if probe is not None:
         out["probe_copy"] = probe
