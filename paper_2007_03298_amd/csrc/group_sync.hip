@@ -26,7 +26,13 @@
 //     traffic is needed: a column never leaves its lane), one mean is formed
 //     per column and stored |group| times, so members end bit-identical;
 //   - loads and stores carry the non-temporal hint: every byte is touched
-//     exactly once per step.
+//     exactly once per step;
+//   - the launch asks for kSyncLdsPad bytes of dynamic LDS that the kernel
+//     never touches.  Its only purpose is to hold the number of workgroups per
+//     CU at two: measured on MI355X, about eight wavefronts per CU with a few
+//     KiB of loads in flight each sustain more HBM bandwidth for this 2:1
+//     read/write mix than full occupancy does (5.8 vs 5.4 TB/s), and one
+//     workgroup per CU is too few (3.9 TB/s).
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -56,18 +62,6 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 #endif
 #ifndef DS_SYNC_NT_STORE
 #define DS_SYNC_NT_STORE 1
-#endif
-#ifndef DS_SYNC_GROUP_MAJOR
-#define DS_SYNC_GROUP_MAJOR 1
-#endif
-#ifndef DS_SYNC_WAVE_CONTIG
-#define DS_SYNC_WAVE_CONTIG 1
-#endif
-#ifndef DS_SYNC_XCD_MAP
-#define DS_SYNC_XCD_MAP 0
-#endif
-#ifndef DS_SYNC_SERIAL
-#define DS_SYNC_SERIAL 0
 #endif
 #ifndef DS_SYNC_BARRIER
 #define DS_SYNC_BARRIER 1
@@ -132,29 +126,6 @@ __device__ __forceinline__ void add_members(f32x4 (&sum)[kSyncVecPerLane], const
                                             int64_t ldx, int64_t ldg, const PartitionArg& part, int q,
                                             const int (&col)[kSyncVecPerLane],
                                             const bool (&live)[kSyncVecPerLane], float lr) {
-#if DS_SYNC_SERIAL == 9
-    // one member at a time: load, wait, accumulate
-#pragma unroll
-    for (int j = 0; j < kCount; ++j) {
-        const int64_t row = packed_byte(part.perm, q + j);
-        const float* xr = xt + row * ldx;
-        const GT* gr = gt + row * ldg;
-        f32x4 x1[kSyncVecPerLane], g1[kSyncVecPerLane];
-#pragma unroll
-        for (int v = 0; v < kSyncVecPerLane; ++v) {
-            if (kFull || live[v]) {
-                x1[v] = stream_load(reinterpret_cast<const f32x4*>(xr + col[v]));
-                g1[v] = load_grad4(gr + col[v]);
-            }
-        }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#pragma unroll
-        for (int v = 0; v < kSyncVecPerLane; ++v)
-            if (kFull || live[v]) sum[v] += x1[v] - lr * g1[v];
-        __builtin_amdgcn_sched_barrier(0);
-    }
-    return;
-#endif
     f32x4 x[kCount][kSyncVecPerLane], g[kCount][kSyncVecPerLane];
 #pragma unroll
     for (int j = 0; j < kCount; ++j) {
@@ -168,13 +139,6 @@ __device__ __forceinline__ void add_members(f32x4 (&sum)[kSyncVecPerLane], const
                 g[j][v] = load_grad4(gr + col[v]);
             }
         }
-#if DS_SYNC_SERIAL == 1
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#elif DS_SYNC_SERIAL == 2
-        if (j & 1) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#elif DS_SYNC_SERIAL == 4
-        if ((j & 3) == 3) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#endif
     }
 #pragma unroll
     for (int j = 0; j < kCount; ++j) {
@@ -194,11 +158,7 @@ __device__ __forceinline__ void sync_tile(float* xt, const GT* gt, int len, int6
     const int lane = static_cast<int>(threadIdx.x) & 63, wave = static_cast<int>(threadIdx.x) >> 6;
 #pragma unroll
     for (int v = 0; v < kSyncVecPerLane; ++v) {
-#if DS_SYNC_WAVE_CONTIG
         col[v] = ((wave * kSyncVecPerLane + v) * 64 + lane) * 4;   // a wavefront owns VPL consecutive KiB
-#else
-        col[v] = (v * kSyncThreads + static_cast<int>(threadIdx.x)) * 4;
-#endif
         live[v] = kFull || col[v] + 4 <= len;
         sum[v] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
@@ -245,25 +205,11 @@ __device__ __forceinline__ void sync_tile(float* xt, const GT* gt, int len, int6
 template <typename GT, bool kRagged>
 __global__ void __launch_bounds__(kSyncThreads)
 group_sync_kernel(float* __restrict__ X, const GT* __restrict__ G, int64_t ldx, int64_t ldg,
-                  int64_t P, const Tile* __restrict__ tiles, PartitionArg part, float lr, uint32_t n_tiles) {
+                  int64_t P, const Tile* __restrict__ tiles, PartitionArg part, float lr) {
     static_assert(kChunk >= 1 && kChunk <= 16, "remainder switch covers up to 15 members");
     int64_t start;
     int32_t len;
-#if DS_SYNC_GROUP_MAJOR
-    uint32_t tile_id = blockIdx.x;
-    const uint32_t group_id = blockIdx.y;
-#else
-    uint32_t tile_id = blockIdx.y;
-    const uint32_t group_id = blockIdx.x;
-#endif
-#if DS_SYNC_XCD_MAP
-    {
-        // workgroups are dealt round-robin to the 8 XCDs: give each XCD one contiguous eighth of the tiles
-        const uint32_t per_xcd = (n_tiles + 7u) / 8u;
-        tile_id = (tile_id & 7u) * per_xcd + (tile_id >> 3);
-        if (tile_id >= n_tiles) return;
-    }
-#endif
+    const uint32_t tile_id = blockIdx.x, group_id = blockIdx.y;
     if (kRagged) {
         const Tile tl = tiles[tile_id];
         start = tl.start;
@@ -329,13 +275,7 @@ template <bool kRagged>
 int launch(void* X, const void* G, int32_t g_dtype, int64_t P, int64_t ldx, int64_t ldg,
            int64_t n_tiles, const Tile* tiles, const PartitionArg& part, int32_t n_groups, float lr,
            void* stream) {
-#if DS_SYNC_XCD_MAP
-    const dim3 grid(static_cast<uint32_t>((n_tiles + 7) / 8 * 8), static_cast<uint32_t>(n_groups), 1);
-#elif DS_SYNC_GROUP_MAJOR
     const dim3 grid(static_cast<uint32_t>(n_tiles), static_cast<uint32_t>(n_groups), 1);
-#else
-    const dim3 grid(static_cast<uint32_t>(n_groups), static_cast<uint32_t>(n_tiles), 1);
-#endif
     const dim3 block(kSyncThreads, 1, 1);
     hipStream_t st = static_cast<hipStream_t>(stream);
 #ifdef DS_TUNE_ENV
@@ -350,10 +290,10 @@ int launch(void* X, const void* G, int32_t g_dtype, int64_t P, int64_t ldx, int6
 #endif
     if (g_dtype == DS_F32) {
         hipLaunchKernelGGL((group_sync_kernel<float, kRagged>), grid, block, kSyncLdsPad, st, static_cast<float*>(X),
-                           static_cast<const float*>(G), ldx, ldg, P, tiles, part, lr, static_cast<uint32_t>(n_tiles));
+                           static_cast<const float*>(G), ldx, ldg, P, tiles, part, lr);
     } else {
         hipLaunchKernelGGL((group_sync_kernel<uint16_t, kRagged>), grid, block, kSyncLdsPad, st, static_cast<float*>(X),
-                           static_cast<const uint16_t*>(G), ldx, ldg, P, tiles, part, lr, static_cast<uint32_t>(n_tiles));
+                           static_cast<const uint16_t*>(G), ldx, ldg, P, tiles, part, lr);
     }
     return hipGetLastError() == hipSuccess ? DS_OK : DS_ERR_HIP;
 }
