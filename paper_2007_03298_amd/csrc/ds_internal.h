@@ -27,17 +27,16 @@ int pack_partition(int32_t W, const int32_t* perm, const int32_t* off, int32_t n
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// Columns handled by one workgroup of the group-sync kernels: 256 lanes, each
-// owning kSyncVecPerLane vectors of 4 consecutive columns.  The ragged plan is
-// cut in the same unit.
-constexpr int kSyncThreads = 256;
-#ifndef DS_SYNC_VPL
-#define DS_SYNC_VPL 1
-#endif
-constexpr int kSyncVecPerLane = DS_SYNC_VPL;
-constexpr int kSyncTileCols = kSyncThreads * 4 * kSyncVecPerLane;
+// Group-sync launch shape.  A workgroup is ONE wavefront; a lane owns vpl
+// vectors of 4 consecutive columns (vpl = 1, 2, 4 or 8, chosen from the group
+// size so that a wavefront keeps kSyncLoadsPerLane 128-bit loads in flight), so
+// a workgroup covers 256*vpl columns of every member row.
+constexpr int kSyncThreads = 64;
+constexpr int kSyncLoadsPerLane = 16;
+// Unit of the ragged plan: 2048 columns = 8 / 4 / 2 / 1 workgroups of vpl 1 / 2 / 4 / 8.
+constexpr int kPlanTileCols = 2048;
 
-// One entry of the ragged plan: a run of at most kSyncTileCols columns that
+// One entry of the ragged plan: a run of at most kPlanTileCols columns that
 // lies inside one segment and starts on a multiple of 8 columns.
 struct Tile {
     int64_t start;

@@ -6,37 +6,36 @@
 // The step is a streaming reduction over the worker axis: 8 (or 6) bytes are
 // read and 4 written per (worker, column) and about one FMA is spent on them,
 // so the kernel is bound by HBM bandwidth and uses no matrix cores.  Mapping:
-//   - a workgroup of 256 lanes owns one tile of kSyncTileCols consecutive
+//   - a workgroup is ONE wavefront and owns a tile of 256*kVpl consecutive
 //     columns of ONE group; blockIdx.y is the group, blockIdx.x the tile, so
 //     consecutive workgroups walk each member row sequentially;
-//   - a lane owns kSyncVecPerLane vectors of 4 consecutive columns, 64 lanes
-//     apart, so every wavefront load/store instruction covers 1 KiB of one
-//     row (128-bit per lane, fully coalesced) and a wavefront owns
-//     kSyncVecPerLane consecutive KiB of every member row;
-//   - member rows are uniform across the workgroup: their indices come from
+//   - a lane owns kVpl vectors of 4 consecutive columns, 64 lanes apart, so
+//     every load/store instruction covers 1 KiB of one row (128-bit per lane,
+//     fully coalesced) and the wavefront owns kVpl consecutive KiB of every
+//     member row;
+//   - member rows are uniform across the wavefront: their indices come from
 //     the kernel-argument block through scalar loads (which have their own
 //     wait counter, so fetching an index never waits for data loads), and the
 //     row base addresses live in scalar registers;
-//   - members are accumulated kChunk at a time, which keeps
-//     2 * kChunk * kSyncVecPerLane 128-bit loads in flight per lane; interior
-//     tiles run a predicate-free body so that those loads issue back to back
-//     (a load guarded by a lane predicate gets its own basic block and the
-//     compiler then waits for it before issuing the next one);
+//   - members are accumulated 8/kVpl at a time, i.e. 16 loads of 1 KiB are in
+//     flight per wavefront whatever the group size (kVpl is picked from it);
+//     interior tiles run a predicate-free body so that those loads issue back
+//     to back (a load guarded by a lane predicate gets its own basic block
+//     and the compiler then waits for it before issuing the next one);
 //   - the reduction over members is sequential inside a lane (no cross-lane
 //     traffic is needed: a column never leaves its lane), one mean is formed
 //     per column and stored |group| times, so members end bit-identical;
 //   - loads and stores carry the non-temporal hint: every byte is touched
 //     exactly once per step;
 //   - the launch asks for kSyncLdsPad bytes of dynamic LDS that the kernel
-//     never touches.  Its only purpose is to hold the number of workgroups per
-//     CU at two: measured on MI355X, about eight wavefronts per CU with a few
-//     KiB of loads in flight each sustain more HBM bandwidth for this 2:1
-//     read/write mix than full occupancy does (5.8 vs 5.4 TB/s), and one
-//     workgroup per CU is too few (3.9 TB/s).
+//     never touches.  Its only purpose is to hold the number of wavefronts per
+//     CU at five (about one per SIMD): measured on MI355X, few independent
+//     wavefronts with 16 KiB of loads in flight each sustain 6.3-6.4 TB/s on
+//     this 2:1 read/write mix, full occupancy 5.4 TB/s, and two wavefronts
+//     per CU 4.4 TB/s.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
-#include <cstdlib>
 #include <utility>
 #include <vector>
 
@@ -44,52 +43,26 @@
 
 namespace {
 
+using ds::kPlanTileCols;
+using ds::kSyncLoadsPerLane;
 using ds::kSyncThreads;
-using ds::kSyncTileCols;
-using ds::kSyncVecPerLane;
 using ds::PartitionArg;
 using ds::Tile;
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-// Tuning constants, fixed at build time from measurements on MI355X.
-#ifndef DS_SYNC_CHUNK
-#define DS_SYNC_CHUNK 2
-#endif
-#ifndef DS_SYNC_NT_LOAD
-#define DS_SYNC_NT_LOAD 1
-#endif
-#ifndef DS_SYNC_NT_STORE
-#define DS_SYNC_NT_STORE 1
-#endif
-#ifndef DS_SYNC_BARRIER
-#define DS_SYNC_BARRIER 1
-#endif
+// Dynamic LDS requested per workgroup (never touched): 160 KiB / 32 KiB = 5 workgroups per CU.
 #ifndef DS_SYNC_LDS_PAD
-#define DS_SYNC_LDS_PAD 65536
+#define DS_SYNC_LDS_PAD 32768
 #endif
-#ifndef DS_TUNE_ENV
 constexpr unsigned kSyncLdsPad = DS_SYNC_LDS_PAD;
-#endif
-constexpr int kChunk = DS_SYNC_CHUNK;  // members accumulated per round of loads
+constexpr int64_t kUncappedWorkgroups = 256 * 32;   // one full-occupancy load of the 256 CUs
 
 template <typename V>
-__device__ __forceinline__ V stream_load(const V* p) {
-#if DS_SYNC_NT_LOAD
-    return __builtin_nontemporal_load(p);
-#else
-    return *p;
-#endif
-}
+__device__ __forceinline__ V stream_load(const V* p) { return __builtin_nontemporal_load(p); }
 template <typename V>
-__device__ __forceinline__ void stream_store(V v, V* p) {
-#if DS_SYNC_NT_STORE
-    __builtin_nontemporal_store(v, p);
-#else
-    *p = v;
-#endif
-}
+__device__ __forceinline__ void stream_store(V v, V* p) { __builtin_nontemporal_store(v, p); }
 
 // Entry i of a packed byte table in the kernel-argument block; i is
 // wavefront-uniform, so this is a scalar load plus scalar bit arithmetic.
@@ -118,22 +91,21 @@ __device__ __forceinline__ float load_grad1(const uint16_t* p) {
 }
 
 // Adds the locally updated parameters x - lr*g of kCount members (perm
-// positions q .. q+kCount-1) to the lane's column sums.  All 2*kCount*VPL
+// positions q .. q+kCount-1) to the lane's column sums.  All 2*kCount*kVpl
 // vector loads are issued back to back before the first use; with kFull
 // nothing is predicated, so the loads sit in one basic block.
-template <typename GT, int kCount, bool kFull>
-__device__ __forceinline__ void add_members(f32x4 (&sum)[kSyncVecPerLane], const float* xt, const GT* gt,
-                                            int64_t ldx, int64_t ldg, const PartitionArg& part, int q,
-                                            const int (&col)[kSyncVecPerLane],
-                                            const bool (&live)[kSyncVecPerLane], float lr) {
-    f32x4 x[kCount][kSyncVecPerLane], g[kCount][kSyncVecPerLane];
+template <typename GT, int kVpl, int kCount, bool kFull>
+__device__ __forceinline__ void add_members(f32x4 (&sum)[kVpl], const float* xt, const GT* gt, int64_t ldx,
+                                            int64_t ldg, const PartitionArg& part, int q, const int (&col)[kVpl],
+                                            const bool (&live)[kVpl], float lr) {
+    f32x4 x[kCount][kVpl], g[kCount][kVpl];
 #pragma unroll
     for (int j = 0; j < kCount; ++j) {
         const int64_t row = packed_byte(part.perm, q + j);
         const float* xr = xt + row * ldx;
         const GT* gr = gt + row * ldg;
 #pragma unroll
-        for (int v = 0; v < kSyncVecPerLane; ++v) {
+        for (int v = 0; v < kVpl; ++v) {
             if (kFull || live[v]) {
                 x[j][v] = stream_load(reinterpret_cast<const f32x4*>(xr + col[v]));
                 g[j][v] = load_grad4(gr + col[v]);
@@ -143,54 +115,53 @@ __device__ __forceinline__ void add_members(f32x4 (&sum)[kSyncVecPerLane], const
 #pragma unroll
     for (int j = 0; j < kCount; ++j) {
 #pragma unroll
-        for (int v = 0; v < kSyncVecPerLane; ++v)
+        for (int v = 0; v < kVpl; ++v)
             if (kFull || live[v]) sum[v] += x[j][v] - lr * g[j][v];
     }
 }
 
-// One tile of one group.  kFull: the tile has all kSyncTileCols columns.
-template <typename GT, bool kFull>
+// One tile of one group.  kFull: the tile has all 256*kVpl columns.
+template <typename GT, int kVpl, bool kFull>
 __device__ __forceinline__ void sync_tile(float* xt, const GT* gt, int len, int64_t ldx, int64_t ldg,
                                           const PartitionArg& part, int first, int n, float lr) {
-    int col[kSyncVecPerLane];
-    bool live[kSyncVecPerLane];
-    f32x4 sum[kSyncVecPerLane];
-    const int lane = static_cast<int>(threadIdx.x) & 63, wave = static_cast<int>(threadIdx.x) >> 6;
+    constexpr int kChunk = kSyncLoadsPerLane / 2 / kVpl;   // members per round of loads
+    int col[kVpl];
+    bool live[kVpl];
+    f32x4 sum[kVpl];
+    const int lane = static_cast<int>(threadIdx.x);
 #pragma unroll
-    for (int v = 0; v < kSyncVecPerLane; ++v) {
-        col[v] = ((wave * kSyncVecPerLane + v) * 64 + lane) * 4;   // a wavefront owns VPL consecutive KiB
+    for (int v = 0; v < kVpl; ++v) {
+        col[v] = (v * 64 + lane) * 4;
         live[v] = kFull || col[v] + 4 <= len;
         sum[v] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
     int q = first;
     const int end = first + n;
     for (; q + kChunk <= end; q += kChunk)
-        add_members<GT, kChunk, kFull>(sum, xt, gt, ldx, ldg, part, q, col, live, lr);
+        add_members<GT, kVpl, kChunk, kFull>(sum, xt, gt, ldx, ldg, part, q, col, live, lr);
     // remaining members (fewer than kChunk): one specialised, branch-free body each
     switch (end - q) {
-#define DS_REST(k) case k: if (k < kChunk) add_members<GT, (k < kChunk ? k : 1), kFull>(sum, xt, gt, ldx, ldg, part, q, col, live, lr); break;
+#define DS_REST(k) \
+    case k:        \
+        if (k < kChunk) add_members<GT, kVpl, (k < kChunk ? k : 1), kFull>(sum, xt, gt, ldx, ldg, part, q, col, live, lr); \
+        break;
         DS_REST(1) DS_REST(2) DS_REST(3) DS_REST(4) DS_REST(5) DS_REST(6) DS_REST(7)
-        DS_REST(8) DS_REST(9) DS_REST(10) DS_REST(11) DS_REST(12) DS_REST(13) DS_REST(14) DS_REST(15)
 #undef DS_REST
         default: break;
     }
     const float nf = static_cast<float>(n);
 #pragma unroll
-    for (int v = 0; v < kSyncVecPerLane; ++v) sum[v] = sum[v] / nf;
-#if DS_SYNC_BARRIER
-    // all four wavefronts switch from reading to writing together
-    __syncthreads();
-#endif
+    for (int v = 0; v < kVpl; ++v) sum[v] = sum[v] / nf;
     for (int m = first; m < end; ++m) {
         float* xr = xt + static_cast<int64_t>(packed_byte(part.perm, m)) * ldx;
 #pragma unroll
-        for (int v = 0; v < kSyncVecPerLane; ++v)
+        for (int v = 0; v < kVpl; ++v)
             if (kFull || live[v]) stream_store(sum[v], reinterpret_cast<f32x4*>(xr + col[v]));
     }
     if (!kFull) {
         // ragged end of the tile: fewer than 4 columns, one lane each
-        const int c = (len & ~3) + static_cast<int>(threadIdx.x);
-        if (threadIdx.x < 3 && c < len) {
+        const int c = (len & ~3) + lane;
+        if (lane < 3 && c < len) {
             float s = 0.f;
             for (int m = first; m < end; ++m) {
                 const int64_t row = packed_byte(part.perm, m);
@@ -202,32 +173,38 @@ __device__ __forceinline__ void sync_tile(float* xt, const GT* gt, int len, int6
     }
 }
 
-template <typename GT, bool kRagged>
+template <typename GT, bool kRagged, int kVpl>
 __global__ void __launch_bounds__(kSyncThreads)
 group_sync_kernel(float* __restrict__ X, const GT* __restrict__ G, int64_t ldx, int64_t ldg,
                   int64_t P, const Tile* __restrict__ tiles, PartitionArg part, float lr) {
-    static_assert(kChunk >= 1 && kChunk <= 16, "remainder switch covers up to 15 members");
+    static_assert(kVpl == 1 || kVpl == 2 || kVpl == 4 || kVpl == 8, "a lane owns 1, 2, 4 or 8 vectors");
+    constexpr int kTileCols = kSyncThreads * 4 * kVpl;
+    const uint32_t tile_id = blockIdx.x, group_id = blockIdx.y;
     int64_t start;
     int32_t len;
-    const uint32_t tile_id = blockIdx.x, group_id = blockIdx.y;
     if (kRagged) {
-        const Tile tl = tiles[tile_id];
-        start = tl.start;
-        len = tl.len;
+        // a plan entry covers up to kPlanTileCols columns: kSub workgroups share it
+        constexpr uint32_t kSub = kPlanTileCols / kTileCols;
+        const Tile tl = tiles[tile_id / kSub];
+        const int32_t done = static_cast<int32_t>(tile_id % kSub) * kTileCols;
         // a table that does not belong to these stacks must not become a wild access
         const int64_t ld_min = ldx < ldg ? ldx : ldg;
-        if (start < 0 || (start & 7) != 0 || len < 0 || len > kSyncTileCols || start > ld_min - len) return;
+        if (tl.start < 0 || (tl.start & 7) != 0 || tl.len < 0 || tl.len > kPlanTileCols || tl.start > ld_min - tl.len)
+            return;
+        if (done >= tl.len) return;
+        start = tl.start + done;
+        len = tl.len - done < kTileCols ? tl.len - done : kTileCols;
     } else {
-        start = static_cast<int64_t>(tile_id) * kSyncTileCols;
+        start = static_cast<int64_t>(tile_id) * kTileCols;
         const int64_t left = P - start;
-        len = left < kSyncTileCols ? static_cast<int32_t>(left) : kSyncTileCols;
+        len = left < kTileCols ? static_cast<int32_t>(left) : kTileCols;
     }
     const int first = packed_byte(part.off, static_cast<int>(group_id));
     const int n = packed_byte(part.off, static_cast<int>(group_id) + 1) - first;
-    if (len == kSyncTileCols)
-        sync_tile<GT, true>(X + start, G + start, len, ldx, ldg, part, first, n, lr);
+    if (len == kTileCols)
+        sync_tile<GT, kVpl, true>(X + start, G + start, len, ldx, ldg, part, first, n, lr);
     else
-        sync_tile<GT, false>(X + start, G + start, len, ldx, ldg, part, first, n, lr);
+        sync_tile<GT, kVpl, false>(X + start, G + start, len, ldx, ldg, part, first, n, lr);
 }
 
 struct SegmentScan {
@@ -245,8 +222,8 @@ SegmentScan scan_segments(const ds_segment* segs, int32_t S, int64_t ldx, int64_
         if (o < 0 || l < 0 || l > INT64_MAX - o) return {DS_ERR_BAD_SHAPE, 0};
         if (o % 8 != 0) return {DS_ERR_ALIGN, 0};
         if (have_ld && (o + l > ldx || o + l > ldg)) return {DS_ERR_BAD_SHAPE, 0};
-        tiles += (l + kSyncTileCols - 1) / kSyncTileCols;
-        if (tiles > INT32_MAX) return {DS_ERR_BAD_SHAPE, 0};
+        tiles += (l + kPlanTileCols - 1) / kPlanTileCols;
+        if (tiles > INT32_MAX / 8) return {DS_ERR_BAD_SHAPE, 0};   // up to 8 workgroups per entry
     }
     return {DS_OK, tiles};
 }
@@ -271,30 +248,46 @@ int check_stacks(const void* X, const void* G, int32_t g_dtype, int64_t ldx, int
     return DS_OK;
 }
 
-template <bool kRagged>
-int launch(void* X, const void* G, int32_t g_dtype, int64_t P, int64_t ldx, int64_t ldg,
-           int64_t n_tiles, const Tile* tiles, const PartitionArg& part, int32_t n_groups, float lr,
-           void* stream) {
+// Vectors per lane for a division whose largest group has `largest` members:
+// 2 * members-per-round * vpl = kSyncLoadsPerLane loads in flight per lane.
+int pick_vpl(int32_t largest) { return largest >= 8 ? 1 : largest >= 4 ? 2 : largest >= 2 ? 4 : 8; }
+
+template <typename GT, bool kRagged, int kVpl>
+void launch_one(float* X, const GT* G, int64_t P, int64_t ldx, int64_t ldg, int64_t n_units, const Tile* tiles,
+                const PartitionArg& part, int32_t n_groups, float lr, hipStream_t st) {
+    // n_units: flat -> columns; ragged -> plan entries
+    constexpr int kTileCols = kSyncThreads * 4 * kVpl;
+    const int64_t n_tiles = kRagged ? n_units * (kPlanTileCols / kTileCols) : (n_units + kTileCols - 1) / kTileCols;
     const dim3 grid(static_cast<uint32_t>(n_tiles), static_cast<uint32_t>(n_groups), 1);
-    const dim3 block(kSyncThreads, 1, 1);
+    // the cap on wavefronts per CU pays off for HBM-sized work; a launch that fits the
+    // chip in one go (cache-resident, latency-bound) is better off without it
+    const unsigned lds_pad = n_tiles * n_groups <= kUncappedWorkgroups ? 0u : kSyncLdsPad;
+    hipLaunchKernelGGL((group_sync_kernel<GT, kRagged, kVpl>), grid, dim3(kSyncThreads, 1, 1), lds_pad, st, X, G,
+                       ldx, ldg, P, tiles, part, lr);
+}
+
+template <typename GT, bool kRagged>
+void launch_vpl(int vpl, float* X, const GT* G, int64_t P, int64_t ldx, int64_t ldg, int64_t n_units,
+                const Tile* tiles, const PartitionArg& part, int32_t n_groups, float lr, hipStream_t st) {
+    switch (vpl) {
+        case 1: launch_one<GT, kRagged, 1>(X, G, P, ldx, ldg, n_units, tiles, part, n_groups, lr, st); break;
+        case 2: launch_one<GT, kRagged, 2>(X, G, P, ldx, ldg, n_units, tiles, part, n_groups, lr, st); break;
+        case 4: launch_one<GT, kRagged, 4>(X, G, P, ldx, ldg, n_units, tiles, part, n_groups, lr, st); break;
+        default: launch_one<GT, kRagged, 8>(X, G, P, ldx, ldg, n_units, tiles, part, n_groups, lr, st); break;
+    }
+}
+
+template <bool kRagged>
+int launch(void* X, const void* G, int32_t g_dtype, int64_t P, int64_t ldx, int64_t ldg, int64_t n_units,
+           const Tile* tiles, const PartitionArg& part, int32_t largest, int32_t n_groups, float lr, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
-#ifdef DS_TUNE_ENV
-    const char* pad_env = getenv("DS_LDS_PAD");
-    const unsigned kSyncLdsPad = pad_env ? static_cast<unsigned>(atoi(pad_env)) : 0u;
-    if (kSyncLdsPad > 65536u) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&group_sync_kernel<float, kRagged>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kSyncLdsPad));
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&group_sync_kernel<uint16_t, kRagged>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kSyncLdsPad));
-    }
-#endif
-    if (g_dtype == DS_F32) {
-        hipLaunchKernelGGL((group_sync_kernel<float, kRagged>), grid, block, kSyncLdsPad, st, static_cast<float*>(X),
-                           static_cast<const float*>(G), ldx, ldg, P, tiles, part, lr);
-    } else {
-        hipLaunchKernelGGL((group_sync_kernel<uint16_t, kRagged>), grid, block, kSyncLdsPad, st, static_cast<float*>(X),
-                           static_cast<const uint16_t*>(G), ldx, ldg, P, tiles, part, lr);
-    }
+    const int vpl = pick_vpl(largest);
+    if (g_dtype == DS_F32)
+        launch_vpl<float, kRagged>(vpl, static_cast<float*>(X), static_cast<const float*>(G), P, ldx, ldg, n_units,
+                                   tiles, part, n_groups, lr, st);
+    else
+        launch_vpl<uint16_t, kRagged>(vpl, static_cast<float*>(X), static_cast<const uint16_t*>(G), P, ldx, ldg,
+                                      n_units, tiles, part, n_groups, lr, st);
     return hipGetLastError() == hipSuccess ? DS_OK : DS_ERR_HIP;
 }
 
@@ -310,10 +303,9 @@ extern "C" int ds_group_sync(void* X, const void* G, int32_t g_dtype, int64_t P,
     int32_t max_size = 0, equal_size = 0;
     rc = ds::pack_partition(W, perm, off, n_groups, &part, &max_size, &equal_size);
     if (rc != DS_OK) return rc;
-    const int64_t n_tiles = (P + kSyncTileCols - 1) / kSyncTileCols;
-    if (n_tiles > INT32_MAX) return DS_ERR_BAD_SHAPE;
-    if (n_tiles == 0) return DS_OK;
-    return launch<false>(X, G, g_dtype, P, ldx, ldg, n_tiles, nullptr, part, n_groups, lr, stream);
+    if (P / (kSyncThreads * 4) >= INT32_MAX) return DS_ERR_BAD_SHAPE;   // grid.x limit at the narrowest tile
+    if (P == 0) return DS_OK;
+    return launch<false>(X, G, g_dtype, P, ldx, ldg, P, nullptr, part, max_size, n_groups, lr, stream);
 }
 
 extern "C" size_t ds_ragged_plan_bytes(const ds_segment* segs, int32_t S) {
@@ -335,10 +327,10 @@ extern "C" int ds_ragged_plan(const ds_segment* segs, int32_t S, int64_t ldx, in
     std::vector<Tile> table;
     table.reserve(static_cast<size_t>(sc.n_tiles));
     for (int32_t s = 0; s < S; ++s) {
-        for (int64_t done = 0; done < segs[s].length; done += kSyncTileCols) {
+        for (int64_t done = 0; done < segs[s].length; done += kPlanTileCols) {
             const int64_t left = segs[s].length - done;
             table.push_back(Tile{segs[s].offset + done,
-                                 static_cast<int32_t>(left < kSyncTileCols ? left : kSyncTileCols), 0});
+                                 static_cast<int32_t>(left < kPlanTileCols ? left : kPlanTileCols), 0});
         }
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -363,6 +355,6 @@ extern "C" int ds_group_sync_ragged(void* X, const void* G, int32_t g_dtype, con
     if (sc.n_tiles == 0) return DS_OK;
     if (!plan || !ds::aligned16(plan) || plan_bytes < static_cast<size_t>(sc.n_tiles) * sizeof(Tile))
         return DS_ERR_WORKSPACE;
-    return launch<true>(X, G, g_dtype, 0, ldx, ldg, sc.n_tiles, static_cast<const Tile*>(plan), part,
+    return launch<true>(X, G, g_dtype, 0, ldx, ldg, sc.n_tiles, static_cast<const Tile*>(plan), part, max_size,
                         n_groups, lr, stream);
 }

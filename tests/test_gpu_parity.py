@@ -171,9 +171,13 @@ def check_ragged(W, sizes, segs, ld, bf16, seed):
 @pytest.mark.parametrize("bf16", [True, False])
 def test_ragged_matches_oracle_small(bf16):
     segs = [(0, 256), (256, 1), (264, 0), (320, 2047), (2368, 2048), (4416, 2049), (6472, 7), (6528, 5000),
-            (16384, 3), (16392, 1023), (17416, 1024), (18440, 1025)]
-    check_ragged(8, [4, 4], segs, 19468, bf16, 21)
-    check_ragged(8, [2, 3, 3], segs[::-1], 19468, bf16, 22)          # any order of the list
+            (16384, 3), (16392, 1023), (17416, 1024), (18440, 1025), (19472, 255), (19728, 256), (19984, 257),
+            (20248, 511), (20760, 512), (21272, 513)]
+    check_ragged(8, [4, 4], segs, 21788, bf16, 21)
+    check_ragged(8, [2, 3, 3], segs[::-1], 21788, bf16, 22)          # any order of the list
+    check_ragged(8, [8], segs, 21788, bf16, 25)                      # one vector per lane
+    check_ragged(8, [2] * 4, segs, 21788, bf16, 26)                  # four vectors per lane
+    check_ragged(8, [1] * 8, segs, 21788, bf16, 27)                  # eight vectors per lane
     check_ragged(32, [4] * 8, [(128 * i, 61 + i) for i in range(40)], 128 * 41, bf16, 23)
 
 
