@@ -49,7 +49,9 @@ typedef enum {
                                the alignment rule stated at the entry point                */
     DS_ERR_DTYPE     = -7,  /* g_dtype is neither DS_F32 nor DS_BF16                       */
     DS_ERR_WORKSPACE = -8,  /* workspace / plan buffer NULL, misaligned or too small       */
-    DS_ERR_HIP       = -9   /* a HIP call or kernel launch failed                          */
+    DS_ERR_HIP       = -9,  /* a HIP call or kernel launch failed                          */
+    DS_ERR_TOPOLOGY  = -10  /* rack table: index outside 0..n_racks-1, an unused rack index,
+                               or a rack whose workers all have NIC contention             */
 } ds_status;
 
 /* gradient element type */
@@ -87,6 +89,55 @@ const char* ds_status_string(int status);
  */
 int ds_partition(uint64_t seed, uint64_t t, int32_t W, const int32_t* sizes, int32_t n_groups,
                  int32_t* perm_out, int32_t* off_out);
+
+/*
+ * ds_pattern -- the paper's own divide-and-shuffle pattern for iteration t,
+ * from the rack of every worker (a second source of divisions next to
+ * ds_partition; the output feeds ds_group_sync unchanged).
+ *
+ * Paper: Sec. III-B.  (1) Static topology: the workers of a rack form an
+ * intra-rack group except one representative per rack; the representatives
+ * form the inter-rack group, so every rack has one connection on its
+ * inter-rack link; the workers of a rack take turns as representative.
+ * (2) Inter-rack link contention: the representative of a delayed rack is
+ * paired with one regular representative (group of two), the other regular
+ * representatives form the large inter-rack group, and the regular partner
+ * changes every iteration.  (3) End-host NIC contention: a delayed worker is
+ * never a representative; it is paired with one regular worker of its rack
+ * (group of two, partner changing every iteration) while the rest of the rack
+ * forms the large intra-rack group.
+ * The prose leaves the rotations open; the ones used (t is the only state):
+ *   representative of rack r   = free_r[t mod |free_r|], free_r = workers of r
+ *                                without NIC contention, ascending index;
+ *   partner of k-th delayed rack = regular[(t+k) mod |regular|] (ascending rack
+ *                                index); delayed racks beyond the number of
+ *                                regular ones are paired among themselves; if
+ *                                no rack or every rack is delayed, all
+ *                                representatives form one group;
+ *   partner of k-th delayed worker of a rack = fast[(t+k) mod |fast|], fast =
+ *                                regular non-representatives of the rack; the
+ *                                rack is split only if |fast| > number of
+ *                                delayed workers (someone is left for the hub).
+ * With a single rack nobody is set apart (one group: plain BSP).
+ * Group order: inter-rack pairs, large inter-rack group, then per rack its
+ * pairs and its large group.
+ *
+ *   W            workers, 1..DS_MAX_W
+ *   rack_of      host [W], rack index of every worker, 0..n_racks-1, every index used
+ *   slow_rack    host [n_racks], non-zero = contention on that rack's inter-rack link
+ *   slow_worker  host [W], non-zero = contention on that worker's NIC
+ *   t            iteration
+ *   perm_out     host [W], off_out host [W+1] (at most W groups), n_groups_out: written
+ * ds_pattern_period writes a period B of the pattern: the division of
+ * iteration t+B equals that of t (Sec. IV-B2: W_k = W_{k+B}).
+ * Host only.  Errors: DS_ERR_NULL, DS_ERR_BAD_W, DS_ERR_TOPOLOGY.
+ */
+int ds_pattern(int32_t W, const int32_t* rack_of, const uint8_t* slow_rack, int32_t n_racks,
+               const uint8_t* slow_worker, uint64_t t, int32_t* perm_out, int32_t* off_out,
+               int32_t* n_groups_out);
+
+int ds_pattern_period(int32_t W, const int32_t* rack_of, const uint8_t* slow_rack, int32_t n_racks,
+                      const uint8_t* slow_worker, uint64_t* period_out);
 
 /*
  * ds_group_sync -- local SGD update fused with the in-group parameter average.

@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libdssync.so")
 DS_F32, DS_BF16 = 0, 1
 DS_MAX_W = 64
 
-EXPORTS = ("ds_status_string", "ds_partition", "ds_group_sync", "ds_ragged_plan_bytes", "ds_ragged_plan",
+EXPORTS = ("ds_status_string", "ds_partition", "ds_pattern", "ds_pattern_period", "ds_group_sync", "ds_ragged_plan_bytes", "ds_ragged_plan",
            "ds_group_sync_ragged", "ds_consensus_workspace_bytes", "ds_consensus", "ds_probe_copy")
 
 
@@ -46,6 +46,11 @@ def _load() -> ctypes.CDLL:
     lib.ds_status_string.argtypes = [ctypes.c_int]
     lib.ds_partition.restype = ctypes.c_int
     lib.ds_partition.argtypes = [u64, u64, i32, i32p, i32, i32p, i32p]
+    u8p = ctypes.POINTER(ctypes.c_uint8)
+    lib.ds_pattern.restype = ctypes.c_int
+    lib.ds_pattern.argtypes = [i32, i32p, u8p, i32, u8p, u64, i32p, i32p, i32p]
+    lib.ds_pattern_period.restype = ctypes.c_int
+    lib.ds_pattern_period.argtypes = [i32, i32p, u8p, i32, u8p, ctypes.POINTER(u64)]
     lib.ds_group_sync.restype = ctypes.c_int
     lib.ds_group_sync.argtypes = [vp, vp, i32, i64, i64, i64, i32, i32p, i32p, i32, ctypes.c_float, vp]
     lib.ds_ragged_plan_bytes.restype = sz
@@ -136,6 +141,39 @@ def ds_partition(seed: int, t: int, W: int, sizes: Sequence[int]) -> Tuple[np.nd
     _check(_lib.ds_partition(seed & (2**64 - 1), t & (2**64 - 1), int(W), _i32p(sz), len(sz), _i32p(perm),
                              _i32p(off)), "ds_partition")
     return perm[:W], off
+
+
+def _u8(a) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a, dtype=np.uint8))
+
+
+def _u8p(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8))
+
+
+def ds_pattern(rack_of: Sequence[int], slow_rack: Sequence[int], slow_worker: Sequence[int],
+               t: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Topology-aware groups of iteration ``t``: ``(perm[W], off[n_groups+1])``."""
+    rk, sr, sw = _i32(rack_of), _u8(slow_rack), _u8(slow_worker)
+    W = len(rk)
+    if len(sw) != W:
+        raise ValueError("slow_worker must have one flag per worker")
+    perm = np.zeros(max(W, 1), dtype=np.int32)
+    off = np.zeros(W + 1, dtype=np.int32)
+    n = ctypes.c_int32(0)
+    _check(_lib.ds_pattern(W, _i32p(rk), _u8p(sr), len(sr), _u8p(sw), t & (2**64 - 1), _i32p(perm), _i32p(off),
+                           ctypes.byref(n)), "ds_pattern")
+    return perm[:W], off[:n.value + 1]
+
+
+def ds_pattern_period(rack_of: Sequence[int], slow_rack: Sequence[int], slow_worker: Sequence[int]) -> int:
+    rk, sr, sw = _i32(rack_of), _u8(slow_rack), _u8(slow_worker)
+    if len(sw) != len(rk):
+        raise ValueError("slow_worker must have one flag per worker")
+    B = ctypes.c_uint64(0)
+    _check(_lib.ds_pattern_period(len(rk), _i32p(rk), _u8p(sr), len(sr), _u8p(sw), ctypes.byref(B)),
+           "ds_pattern_period")
+    return int(B.value)
 
 
 def ds_group_sync(X, G, g_dtype: int, P: int, ldx: int, ldg: int, W: int, perm, off, lr: float,

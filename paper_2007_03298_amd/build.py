@@ -15,7 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdssync.so")
-SOURCES = ["partition.cpp", "group_sync.hip", "consensus.hip", "probe.hip"]
+SOURCES = ["partition.cpp", "pattern.cpp", "group_sync.hip", "consensus.hip", "probe.hip"]
 
 
 def hipcc() -> str:

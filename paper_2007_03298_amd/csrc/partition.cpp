@@ -16,6 +16,7 @@ extern "C" const char* ds_status_string(int status) {
         case DS_ERR_DTYPE: return "DS_ERR_DTYPE: unknown gradient element type";
         case DS_ERR_WORKSPACE: return "DS_ERR_WORKSPACE: workspace or plan buffer missing, misaligned or too small";
         case DS_ERR_HIP: return "DS_ERR_HIP: HIP call or kernel launch failed";
+        case DS_ERR_TOPOLOGY: return "DS_ERR_TOPOLOGY: rack table is not a usable topology";
         default: return "unknown ds_status";
     }
 }

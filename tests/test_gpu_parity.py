@@ -276,3 +276,36 @@ def test_config1_trajectory_and_consensus():
             np.testing.assert_allclose(d, expect, rtol=0.01)
     assert worst_step <= TOL_F32 and worst_traj <= TOL_F32
     np.testing.assert_allclose(gpu_consensus(X, cfg.P, cfg.P, cfg.W), oracle.consensus(Xo), rtol=1e-5)
+
+
+# ---------------------------------------------------------------- the paper's own pattern through the GPU path
+
+def test_topology_pattern_drives_the_gpu_step():
+    from oracle import mixing, pattern
+    rack_of, slow_rack, slow_worker = [0, 0, 0, 0, 0, 1, 1, 1], [1, 0], [0, 0, 0, 0, 1, 0, 0, 0]
+    W, P, ld = 8, 50001, 50004
+    B = ds.ds_pattern_period(rack_of, slow_rack, slow_worker)
+    X, G = random_stacks(61, W, ld, ld, False)
+    Gh = wl.tensor_to_numpy(G)
+    Xo = wl.tensor_to_numpy(X)
+    for t in range(B):
+        perm, off = ds.ds_pattern(rack_of, slow_rack, slow_worker, t)
+        po, oo = pattern.partition(rack_of, slow_rack, slow_worker, t)
+        assert perm.tolist() == po and off.tolist() == oo
+        ds.ds_group_sync(X, G, ds.DS_F32, P, ld, ld, W, perm, off, 0.01)
+        oracle.step(Xo, Gh, po, oo, 0.01, 0, P)
+    torch.cuda.synchronize()
+    got = wl.tensor_to_numpy(X)
+    assert scaled_error(got[:, :P], Xo[:, :P]) <= TOL_F32
+    # pure averaging over whole periods contracts the consensus norm as Lemma 1 bounds it
+    mats = [mixing.mixing_matrix(*pattern.partition(rack_of, slow_rack, slow_worker, t)) for t in range(B)]
+    sigma = mixing.contraction_norm(mixing.product(mats))
+    assert sigma < 1.0
+    fro2 = float((got[:, :P].astype(np.float64)**2).sum())
+    Z = torch.zeros_like(G)
+    for k in range(1, 4):
+        for t in range(B):
+            perm, off = ds.ds_pattern(rack_of, slow_rack, slow_worker, t)
+            ds.ds_group_sync(X, Z, ds.DS_F32, P, ld, ld, W, perm, off, 0.0)
+        d = gpu_consensus(X, P, ld, W)
+        assert np.all(d**2 <= sigma**(2 * k) * fro2 * (1 + 1e-5) + 1e-9)

@@ -174,3 +174,63 @@ def test_consensus_argument_errors():
     assert status(ws=0) == -8
     assert status(ws_bytes=need - 1) == -8
     assert status(ws=3 * B + 8) == -8
+
+
+# ---- topology-aware pattern: library against the oracle's independent implementation ----
+
+def random_topology(r):
+    R = int(r.integers(1, 7))
+    sizes = r.integers(1, 9, size=R)
+    rack_of = [k for k in range(R) for _ in range(int(sizes[k]))]
+    W = len(rack_of)
+    slow_rack = (r.random(R) < 0.3).astype(int).tolist()
+    slow_worker = (r.random(W) < 0.25).astype(int).tolist()
+    for k in range(R):
+        members = [w for w in range(W) if rack_of[w] == k]
+        if all(slow_worker[w] for w in members):
+            slow_worker[members[int(r.integers(0, len(members)))]] = 0
+    order = r.permutation(W)                     # workers of a rack need not be contiguous
+    return [rack_of[i] for i in order], slow_rack, [slow_worker[i] for i in order]
+
+
+def test_pattern_bit_exact_against_oracle_on_random_topologies():
+    from oracle import pattern
+    r = np.random.default_rng(77)
+    for _ in range(2000):
+        rack_of, slow_rack, slow_worker = random_topology(r)
+        B = ds.ds_pattern_period(rack_of, slow_rack, slow_worker)
+        assert B == pattern.period(rack_of, slow_rack, slow_worker)
+        for t in [0, 1, 2, int(r.integers(0, 1000)), B, int(r.integers(0, 2**62))]:
+            perm, off = ds.ds_pattern(rack_of, slow_rack, slow_worker, t)
+            p2, o2 = pattern.partition(rack_of, slow_rack, slow_worker, t)
+            assert perm.tolist() == p2 and off.tolist() == o2
+
+
+def test_pattern_testbed_layouts():
+    # the three worker layouts of the paper's testbed (Sec. V-A5)
+    static = ([0, 0, 0, 0, 1, 1, 1, 1], [0, 0], [0] * 8)
+    nic = ([0, 0, 0, 0, 0, 1, 1, 1], [1, 0], [0, 0, 0, 0, 1, 0, 0, 0])
+    for t in range(8):
+        perm, off = ds.ds_pattern(*static, t)
+        assert sorted(np.diff(off).tolist()) == [2, 3, 3]
+        assert perm[:2].tolist() == [t % 4, 4 + t % 4]
+        perm, off = ds.ds_pattern(*nic, t)
+        assert sorted(np.diff(off).tolist()) == [2, 2, 2, 2]
+    assert ds.ds_pattern_period(*static) == 4
+    assert ds.ds_pattern_period(*nic) == 12
+
+
+def test_pattern_errors():
+    def status(*a):
+        with pytest.raises(ds.DsError) as e:
+            ds.ds_pattern(*a)
+        return e.value.status
+    assert status([0, 0, 1], [0, 0], [0, 0, 1], 0) == -10        # rack 1 has only a delayed worker
+    assert status([0, 2], [0, 0, 0], [0, 0], 0) == -10           # rack 1 unused
+    assert status([0, 3], [0, 0], [0, 0], 0) == -10              # rack index out of range
+    assert status([0, -1], [0, 0], [0, 0], 0) == -10
+    assert status([], [0], [], 0) == -2
+    assert status([0] * 65, [0], [0] * 65, 0) == -2
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_pattern_period([0, 2], [0, 0, 0], [0, 0])
+    assert e.value.status == -10
