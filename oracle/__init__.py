@@ -53,6 +53,12 @@ def _load():
         lib.orc_step.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int64,
                                  ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32,
                                  i32p, i32p, ctypes.c_int32, ctypes.c_float]
+        lib.orc_step_opt.restype = ctypes.c_int
+        lib.orc_step_opt.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p,
+                                     ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                     ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32, i32p, i32p,
+                                     ctypes.c_int32, ctypes.c_float, ctypes.c_float, ctypes.c_float,
+                                     ctypes.c_float]
         lib.orc_consensus.restype = ctypes.c_int
         lib.orc_consensus.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
                                       ctypes.c_int32, ctypes.c_void_p]
@@ -126,6 +132,41 @@ def step(X: np.ndarray, G: np.ndarray, perm, off, lr: float,
                           _ptr(perm), _ptr(off), len(off) - 1, ctypes.c_float(lr))
     if rc != 0:
         raise MemoryError("orc_step failed")
+
+
+def step_opt(X: np.ndarray, G: np.ndarray, perm, off, lr: float, V: np.ndarray | None = None,
+             momentum: float = 0.0, weight_decay: float = 0.0, S: np.ndarray | None = None,
+             factor: float = 0.0, col0: int = 0, ncols: int | None = None) -> None:
+    """One step with momentum / weight decay on the local update (buffers ``V``,
+    fp32 ``[W, ldv]``, local to each worker) and the SWA moving average ``S``
+    (fp32 ``[W, lds]``) of Listing 1; in place on ``X``, ``V`` and ``S``."""
+    if X.dtype != np.float32 or X.ndim != 2 or not X.flags.c_contiguous:
+        raise TypeError("X must be a C-contiguous fp32 [W, ld] array")
+    if G.ndim != 2 or not G.flags.c_contiguous or G.shape[0] != X.shape[0] or G.dtype not in (np.float32, np.uint16):
+        raise TypeError("G must be a C-contiguous [W, ld] float32 or uint16 (bf16 bits) array")
+    W, ldx = X.shape
+    width = min(ldx, G.shape[1])
+    for A in (V, S):
+        if A is not None:
+            if A.dtype != np.float32 or A.ndim != 2 or not A.flags.c_contiguous or A.shape[0] != W:
+                raise TypeError("V and S must be C-contiguous fp32 [W, ld] arrays")
+            width = min(width, A.shape[1])
+    if ncols is None:
+        ncols = width - col0
+    if col0 < 0 or ncols < 0 or col0 + ncols > width:
+        raise ValueError("column range outside the arrays")
+    perm = _i32(perm)
+    off = _i32(off)
+    if sorted(perm.tolist()) != list(range(W)) or off[0] != 0 or off[-1] != W or np.any(np.diff(off) < 1):
+        raise ValueError("not a division of the workers into non-empty groups")
+    rc = _load().orc_step_opt(X.ctypes.data, G.ctypes.data, 1 if G.dtype == np.uint16 else 0,
+                              V.ctypes.data if V is not None else None, S.ctypes.data if S is not None else None,
+                              col0, ncols, ldx, G.shape[1], V.shape[1] if V is not None else 0,
+                              S.shape[1] if S is not None else 0, W, _ptr(perm), _ptr(off), len(off) - 1,
+                              ctypes.c_float(lr), ctypes.c_float(momentum), ctypes.c_float(weight_decay),
+                              ctypes.c_float(factor))
+    if rc != 0:
+        raise MemoryError("orc_step_opt failed")
 
 
 def consensus(X: np.ndarray, P: int | None = None) -> np.ndarray:

@@ -170,6 +170,63 @@ int orc_step(float *X, const void *G, int g_is_bf16, int64_t col0, int64_t ncols
 }
 
 /* ------------------------------------------------------------------------- */
+/* One step with the fuller local optimizer and the SWA ensemble of           */
+/* Listing 1.  Sec. V-A3 keeps the hyper-parameters of the original model     */
+/* papers (SGD with momentum and weight decay for the WideResNets); Listing 1 */
+/* hands only the model to Average(), so the momentum buffer stays local.     */
+/* For every worker i and column p:                                           */
+/*     d   = g + weight_decay * x                                             */
+/*     v'  = momentum * v + d            (V absent: v' = d)                    */
+/*     y_i = x - lr * v'                                                       */
+/* then the group mean m of the y_i replaces x for every member, and          */
+/*     s'  = factor * s + (1 - factor) * m      (Listing 1: SWA_model update)  */
+/* V and S are fp32 state, one row per worker, and may each be NULL.          */
+/* ------------------------------------------------------------------------- */
+int orc_step_opt(float *X, const void *G, int g_is_bf16, float *V, float *S, int64_t col0, int64_t ncols,
+                 int64_t ldx, int64_t ldg, int64_t ldv, int64_t lds, int32_t W, const int32_t *perm,
+                 const int32_t *off, int32_t n_groups, float lr, float momentum, float weight_decay,
+                 float factor)
+{
+    const double lrd = (double)lr, mud = (double)momentum, wdd = (double)weight_decay, fd = (double)factor;
+    const float *Gf = (const float *)G;
+    const uint16_t *Gh = (const uint16_t *)G;
+    int32_t *members = (int32_t *)malloc(sizeof(int32_t) * (size_t)W);
+    if (!members) return -2;
+
+    for (int32_t k = 0; k < n_groups; ++k) {
+        const int32_t n = off[k + 1] - off[k];
+        for (int32_t q = 0; q < n; ++q) members[q] = perm[off[k] + q];
+        qsort(members, (size_t)n, sizeof(int32_t), cmp_i32);
+
+#pragma omp parallel for schedule(static)
+        for (int64_t p = col0; p < col0 + ncols; ++p) {
+            double acc = 0.0;
+            for (int32_t q = 0; q < n; ++q) {
+                const int64_t i = members[q];
+                const double x = (double)X[i * ldx + p];
+                const double g = g_is_bf16 ? bf16_bits_to_double(Gh[i * ldg + p])
+                                           : (double)Gf[i * ldg + p];
+                const double d = g + wdd * x;
+                double v = d;
+                if (V) {
+                    v = mud * (double)V[i * ldv + p] + d;
+                    V[i * ldv + p] = (float)v;
+                }
+                acc += x - lrd * v;
+            }
+            const float m = (float)(acc / (double)n);
+            for (int32_t q = 0; q < n; ++q) {
+                const int64_t i = members[q];
+                X[i * ldx + p] = m;
+                if (S) S[i * lds + p] = (float)(fd * (double)S[i * lds + p] + (1.0 - fd) * (double)m);
+            }
+        }
+    }
+    free(members);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
 /* Consensus deviation (Lemma 1's left side, un-squared, per worker):        */
 /*     xbar[p] = (1/W) sum_i X[i,p];  d_i = sqrt( sum_p (X[i,p]-xbar[p])^2 ) */
 /* ------------------------------------------------------------------------- */
