@@ -206,6 +206,49 @@ int ds_group_sync_ragged(void* X, const void* G, int32_t g_dtype, const ds_segme
                          size_t plan_bytes, void* stream);
 
 /*
+ * ds_group_sync_opt / ds_group_sync_ragged_opt -- the same step with the fuller
+ * local optimizer and the SWA ensemble.
+ *
+ * Paper: Listing 1 (optimizer.step(); Average(model, group); SWA_model =
+ * factor*SWA_model + (1-factor)*model) and Sec. V-A3 (hyper-parameters of the
+ * original model papers, i.e. SGD with momentum and weight decay for the
+ * WideResNets).  Only the model is handed to Average, so the momentum buffer
+ * stays local to its worker and is never averaged.  Per worker i, column p:
+ *     d  = G[i,p] + weight_decay * X[i,p]
+ *     v' = momentum * V[i,p] + d;  V[i,p] = v'       (V == NULL: v' = d)
+ *     y_i = X[i,p] - lr * v'
+ * then m = mean of the y_i over the group, X[i,p] = m for every member, and
+ *     S[i,p] = swa_factor * S[i,p] + (1 - swa_factor) * m      (S != NULL)
+ * all in the one fused pass: V and S add a read and a write of 4 bytes each
+ * per (worker, column).  opt == NULL, or V == S == NULL with weight_decay == 0,
+ * is exactly ds_group_sync.  The final model of Listing 1 (average of all SWA
+ * models) is one ds_group_sync over S with a single group of W workers, a zero
+ * gradient stack and lr = 0.
+ *   V, S     dev fp32 [W, ldv] / [W, lds], in/out, 16-byte aligned, leading
+ *            dimension >= P (ragged: >= end of the last segment) and a
+ *            multiple of 4; must not overlap X, G or each other
+ * Other arguments and errors as ds_group_sync / ds_group_sync_ragged.
+ */
+typedef struct {
+    void*   V;             /* momentum buffers, or NULL                       */
+    int64_t ldv;
+    float   momentum;      /* used only when V != NULL                        */
+    float   weight_decay;
+    void*   S;             /* SWA models, or NULL                             */
+    int64_t lds;
+    float   swa_factor;    /* used only when S != NULL                        */
+} ds_local_opt;
+
+int ds_group_sync_opt(void* X, const void* G, int32_t g_dtype, int64_t P, int64_t ldx, int64_t ldg,
+                      int32_t W, const int32_t* perm, const int32_t* off, int32_t n_groups, float lr,
+                      const ds_local_opt* opt, void* stream);
+
+int ds_group_sync_ragged_opt(void* X, const void* G, int32_t g_dtype, const ds_segment* segs, int32_t S,
+                             int64_t ldx, int64_t ldg, int32_t W, const int32_t* perm,
+                             const int32_t* off, int32_t n_groups, float lr, const ds_local_opt* opt,
+                             const void* plan, size_t plan_bytes, void* stream);
+
+/*
  * ds_consensus -- how far every replica is from the mean replica.
  *
  * Paper: Sec. IV-B2; the left-hand side of Lemma 1 for worker i, un-squared:

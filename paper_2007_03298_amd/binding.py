@@ -21,13 +21,19 @@ DS_F32, DS_BF16 = 0, 1
 DS_MAX_W = 64
 
 EXPORTS = ("ds_status_string", "ds_partition", "ds_pattern", "ds_pattern_period", "ds_group_sync", "ds_ragged_plan_bytes", "ds_ragged_plan",
-           "ds_group_sync_ragged", "ds_consensus_workspace_bytes", "ds_consensus", "ds_probe_copy")
+           "ds_group_sync_ragged", "ds_group_sync_opt", "ds_group_sync_ragged_opt", "ds_consensus_workspace_bytes", "ds_consensus", "ds_probe_copy")
 
 
 class DsError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
         super().__init__("%s failed: %s (%d)" % (where, status_string(status), status))
+
+
+class ds_local_opt(ctypes.Structure):
+    _fields_ = [("V", ctypes.c_void_p), ("ldv", ctypes.c_int64), ("momentum", ctypes.c_float),
+                ("weight_decay", ctypes.c_float), ("S", ctypes.c_void_p), ("lds", ctypes.c_int64),
+                ("swa_factor", ctypes.c_float)]
 
 
 class ds_segment(ctypes.Structure):
@@ -60,6 +66,12 @@ def _load() -> ctypes.CDLL:
     lib.ds_group_sync_ragged.restype = ctypes.c_int
     lib.ds_group_sync_ragged.argtypes = [vp, vp, i32, segp, i32, i64, i64, i32, i32p, i32p, i32,
                                          ctypes.c_float, vp, sz, vp]
+    optp = ctypes.POINTER(ds_local_opt)
+    lib.ds_group_sync_opt.restype = ctypes.c_int
+    lib.ds_group_sync_opt.argtypes = [vp, vp, i32, i64, i64, i64, i32, i32p, i32p, i32, ctypes.c_float, optp, vp]
+    lib.ds_group_sync_ragged_opt.restype = ctypes.c_int
+    lib.ds_group_sync_ragged_opt.argtypes = [vp, vp, i32, segp, i32, i64, i64, i32, i32p, i32p, i32,
+                                             ctypes.c_float, optp, vp, sz, vp]
     lib.ds_consensus_workspace_bytes.restype = sz
     lib.ds_consensus_workspace_bytes.argtypes = [i32, i64]
     lib.ds_consensus.restype = ctypes.c_int
@@ -200,6 +212,29 @@ def ds_group_sync_ragged(X, G, g_dtype: int, segments, ldx: int, ldg: int, W: in
     _check(_lib.ds_group_sync_ragged(_addr(X), _addr(G), g_dtype, arr, S, ldx, ldg, W, _i32p(perm), _i32p(off),
                                      len(off) - 1, lr, _addr(plan), plan_bytes, _stream(stream)),
            "ds_group_sync_ragged")
+
+
+def local_opt(V=None, ldv: int = 0, momentum: float = 0.0, weight_decay: float = 0.0, S=None, lds: int = 0,
+              swa_factor: float = 0.0) -> ds_local_opt:
+    """Fill a ``ds_local_opt`` (momentum buffers ``V``, SWA models ``S``; either may be None)."""
+    return ds_local_opt(_addr(V) or None, ldv, momentum, weight_decay, _addr(S) or None, lds, swa_factor)
+
+
+def ds_group_sync_opt(X, G, g_dtype: int, P: int, ldx: int, ldg: int, W: int, perm, off, lr: float,
+                      opt: ds_local_opt | None, stream=None) -> None:
+    perm, off = _i32(perm), _i32(off)
+    _check(_lib.ds_group_sync_opt(_addr(X), _addr(G), g_dtype, P, ldx, ldg, W, _i32p(perm), _i32p(off),
+                                  len(off) - 1, lr, ctypes.byref(opt) if opt is not None else None,
+                                  _stream(stream)), "ds_group_sync_opt")
+
+
+def ds_group_sync_ragged_opt(X, G, g_dtype: int, segments, ldx: int, ldg: int, W: int, perm, off, lr: float,
+                             opt: ds_local_opt | None, plan, plan_bytes: int, stream=None) -> None:
+    arr, S = segments if isinstance(segments, tuple) and isinstance(segments[1], int) else _segs(segments)
+    perm, off = _i32(perm), _i32(off)
+    _check(_lib.ds_group_sync_ragged_opt(_addr(X), _addr(G), g_dtype, arr, S, ldx, ldg, W, _i32p(perm), _i32p(off),
+                                         len(off) - 1, lr, ctypes.byref(opt) if opt is not None else None,
+                                         _addr(plan), plan_bytes, _stream(stream)), "ds_group_sync_ragged_opt")
 
 
 def pack_segments(segments):

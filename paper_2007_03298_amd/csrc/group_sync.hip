@@ -90,15 +90,27 @@ __device__ __forceinline__ float load_grad1(const uint16_t* p) {
     return bits_to_f32(static_cast<uint32_t>(*p) << 16);
 }
 
-// Adds the locally updated parameters x - lr*g of kCount members (perm
-// positions q .. q+kCount-1) to the lane's column sums.  All 2*kCount*kVpl
-// vector loads are issued back to back before the first use; with kFull
-// nothing is predicated, so the loads sit in one basic block.
-template <typename GT, int kVpl, int kCount, bool kFull>
+// Optional per-worker state of the fuller local step (Listing 1; Sec. V-A3):
+// momentum buffers V (never averaged: only the model is handed to Average) and
+// SWA models S.  tile-relative pointers, NULL-free when the matching flag is set.
+struct Extras {
+    float* v;
+    float* s;
+    int64_t ldv, lds;
+    float momentum, weight_decay, factor;
+};
+
+// Adds the locally updated parameters of kCount members (perm positions
+// q .. q+kCount-1) to the lane's column sums.  Plain step: y = x - lr*g.
+// With kOpt: d = g + weight_decay*x; kHasV: v' = momentum*v + d is stored back
+// and y = x - lr*v', else y = x - lr*d.  All vector loads are issued back to
+// back before the first use; with kFull nothing is predicated, so the loads
+// sit in one basic block.
+template <typename GT, int kVpl, int kCount, bool kFull, bool kOpt, bool kHasV>
 __device__ __forceinline__ void add_members(f32x4 (&sum)[kVpl], const float* xt, const GT* gt, int64_t ldx,
-                                            int64_t ldg, const PartitionArg& part, int q, const int (&col)[kVpl],
-                                            const bool (&live)[kVpl], float lr) {
-    f32x4 x[kCount][kVpl], g[kCount][kVpl];
+                                            int64_t ldg, const Extras& ex, const PartitionArg& part, int q,
+                                            const int (&col)[kVpl], const bool (&live)[kVpl], float lr) {
+    f32x4 x[kCount][kVpl], g[kCount][kVpl], mv[kHasV ? kCount : 1][kVpl];
 #pragma unroll
     for (int j = 0; j < kCount; ++j) {
         const int64_t row = packed_byte(part.perm, q + j);
@@ -109,21 +121,67 @@ __device__ __forceinline__ void add_members(f32x4 (&sum)[kVpl], const float* xt,
             if (kFull || live[v]) {
                 x[j][v] = stream_load(reinterpret_cast<const f32x4*>(xr + col[v]));
                 g[j][v] = load_grad4(gr + col[v]);
+                if (kHasV) mv[j][v] = stream_load(reinterpret_cast<const f32x4*>(ex.v + row * ex.ldv + col[v]));
             }
         }
     }
 #pragma unroll
     for (int j = 0; j < kCount; ++j) {
+        const int64_t row = kHasV ? packed_byte(part.perm, q + j) : 0;
 #pragma unroll
-        for (int v = 0; v < kVpl; ++v)
-            if (kFull || live[v]) sum[v] += x[j][v] - lr * g[j][v];
+        for (int v = 0; v < kVpl; ++v) {
+            if (kFull || live[v]) {
+                if (!kOpt) {
+                    sum[v] += x[j][v] - lr * g[j][v];
+                } else {
+                    f32x4 d = g[j][v] + ex.weight_decay * x[j][v];
+                    if (kHasV) {
+                        d = ex.momentum * mv[j][v] + d;
+                        stream_store(d, reinterpret_cast<f32x4*>(ex.v + row * ex.ldv + col[v]));
+                    }
+                    sum[v] += x[j][v] - lr * d;
+                }
+            }
+        }
+    }
+}
+
+// Writes the mean to kCount members; with kHasS also moves their SWA models:
+// s' = factor*s + (1-factor)*mean (the S loads are issued together first).
+template <int kVpl, int kCount, bool kFull, bool kHasS>
+__device__ __forceinline__ void store_members(const f32x4 (&mean)[kVpl], float* xt, int64_t ldx, const Extras& ex,
+                                              const PartitionArg& part, int q, const int (&col)[kVpl],
+                                              const bool (&live)[kVpl]) {
+    f32x4 s[kHasS ? kCount : 1][kVpl];
+    if (kHasS) {
+#pragma unroll
+        for (int j = 0; j < kCount; ++j) {
+            const int64_t row = packed_byte(part.perm, q + j);
+#pragma unroll
+            for (int v = 0; v < kVpl; ++v)
+                if (kFull || live[v]) s[j][v] = stream_load(reinterpret_cast<const f32x4*>(ex.s + row * ex.lds + col[v]));
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < kCount; ++j) {
+        const int64_t row = packed_byte(part.perm, q + j);
+#pragma unroll
+        for (int v = 0; v < kVpl; ++v) {
+            if (kFull || live[v]) {
+                stream_store(mean[v], reinterpret_cast<f32x4*>(xt + row * ldx + col[v]));
+                if (kHasS) {
+                    const f32x4 moved = ex.factor * s[j][v] + (1.0f - ex.factor) * mean[v];
+                    stream_store(moved, reinterpret_cast<f32x4*>(ex.s + row * ex.lds + col[v]));
+                }
+            }
+        }
     }
 }
 
 // One tile of one group.  kFull: the tile has all 256*kVpl columns.
-template <typename GT, int kVpl, bool kFull>
+template <typename GT, int kVpl, bool kFull, bool kOpt, bool kHasV, bool kHasS>
 __device__ __forceinline__ void sync_tile(float* xt, const GT* gt, int len, int64_t ldx, int64_t ldg,
-                                          const PartitionArg& part, int first, int n, float lr) {
+                                          const Extras& ex, const PartitionArg& part, int first, int n, float lr) {
     constexpr int kChunk = kSyncLoadsPerLane / 2 / kVpl;   // members per round of loads
     int col[kVpl];
     bool live[kVpl];
@@ -138,12 +196,14 @@ __device__ __forceinline__ void sync_tile(float* xt, const GT* gt, int len, int6
     int q = first;
     const int end = first + n;
     for (; q + kChunk <= end; q += kChunk)
-        add_members<GT, kVpl, kChunk, kFull>(sum, xt, gt, ldx, ldg, part, q, col, live, lr);
+        add_members<GT, kVpl, kChunk, kFull, kOpt, kHasV>(sum, xt, gt, ldx, ldg, ex, part, q, col, live, lr);
     // remaining members (fewer than kChunk): one specialised, branch-free body each
     switch (end - q) {
 #define DS_REST(k) \
     case k:        \
-        if (k < kChunk) add_members<GT, kVpl, (k < kChunk ? k : 1), kFull>(sum, xt, gt, ldx, ldg, part, q, col, live, lr); \
+        if (k < kChunk) \
+            add_members<GT, kVpl, (k < kChunk ? k : 1), kFull, kOpt, kHasV>(sum, xt, gt, ldx, ldg, ex, part, q, col, \
+                                                                            live, lr);                              \
         break;
         DS_REST(1) DS_REST(2) DS_REST(3) DS_REST(4) DS_REST(5) DS_REST(6) DS_REST(7)
 #undef DS_REST
@@ -152,32 +212,48 @@ __device__ __forceinline__ void sync_tile(float* xt, const GT* gt, int len, int6
     const float nf = static_cast<float>(n);
 #pragma unroll
     for (int v = 0; v < kVpl; ++v) sum[v] = sum[v] / nf;
-    for (int m = first; m < end; ++m) {
-        float* xr = xt + static_cast<int64_t>(packed_byte(part.perm, m)) * ldx;
-#pragma unroll
-        for (int v = 0; v < kVpl; ++v)
-            if (kFull || live[v]) stream_store(sum[v], reinterpret_cast<f32x4*>(xr + col[v]));
+    if (!kHasS) {
+        for (int m = first; m < end; ++m) store_members<kVpl, 1, kFull, false>(sum, xt, ldx, ex, part, m, col, live);
+    } else {
+        int m = first;
+        for (; m + kChunk <= end; m += kChunk)
+            store_members<kVpl, kChunk, kFull, true>(sum, xt, ldx, ex, part, m, col, live);
+        for (; m < end; ++m) store_members<kVpl, 1, kFull, true>(sum, xt, ldx, ex, part, m, col, live);
     }
     if (!kFull) {
         // ragged end of the tile: fewer than 4 columns, one lane each
         const int c = (len & ~3) + lane;
         if (lane < 3 && c < len) {
-            float s = 0.f;
+            float acc = 0.f;
             for (int m = first; m < end; ++m) {
                 const int64_t row = packed_byte(part.perm, m);
-                s += xt[row * ldx + c] - lr * load_grad1(gt + row * ldg + c);
+                const float x = xt[row * ldx + c];
+                float d = load_grad1(gt + row * ldg + c);
+                if (kOpt) {
+                    d = d + ex.weight_decay * x;
+                    if (kHasV) {
+                        d = ex.momentum * ex.v[row * ex.ldv + c] + d;
+                        ex.v[row * ex.ldv + c] = d;
+                    }
+                }
+                acc += x - lr * d;
             }
-            s = s / nf;
-            for (int m = first; m < end; ++m) xt[static_cast<int64_t>(packed_byte(part.perm, m)) * ldx + c] = s;
+            acc = acc / nf;
+            for (int m = first; m < end; ++m) {
+                const int64_t row = packed_byte(part.perm, m);
+                xt[row * ldx + c] = acc;
+                if (kHasS) ex.s[row * ex.lds + c] = ex.factor * ex.s[row * ex.lds + c] + (1.0f - ex.factor) * acc;
+            }
         }
     }
 }
 
-template <typename GT, bool kRagged, int kVpl>
+template <typename GT, bool kRagged, int kVpl, bool kOpt, bool kHasV, bool kHasS>
 __global__ void __launch_bounds__(kSyncThreads)
 group_sync_kernel(float* __restrict__ X, const GT* __restrict__ G, int64_t ldx, int64_t ldg,
-                  int64_t P, const Tile* __restrict__ tiles, PartitionArg part, float lr) {
+                  int64_t P, const Tile* __restrict__ tiles, PartitionArg part, float lr, Extras ex) {
     static_assert(kVpl == 1 || kVpl == 2 || kVpl == 4 || kVpl == 8, "a lane owns 1, 2, 4 or 8 vectors");
+    static_assert(kOpt || (!kHasV && !kHasS), "extra state implies the extended step");
     constexpr int kTileCols = kSyncThreads * 4 * kVpl;
     const uint32_t tile_id = blockIdx.x, group_id = blockIdx.y;
     int64_t start;
@@ -188,7 +264,9 @@ group_sync_kernel(float* __restrict__ X, const GT* __restrict__ G, int64_t ldx, 
         const Tile tl = tiles[tile_id / kSub];
         const int32_t done = static_cast<int32_t>(tile_id % kSub) * kTileCols;
         // a table that does not belong to these stacks must not become a wild access
-        const int64_t ld_min = ldx < ldg ? ldx : ldg;
+        int64_t ld_min = ldx < ldg ? ldx : ldg;
+        if (kHasV && ex.ldv < ld_min) ld_min = ex.ldv;
+        if (kHasS && ex.lds < ld_min) ld_min = ex.lds;
         if (tl.start < 0 || (tl.start & 7) != 0 || tl.len < 0 || tl.len > kPlanTileCols || tl.start > ld_min - tl.len)
             return;
         if (done >= tl.len) return;
@@ -199,12 +277,14 @@ group_sync_kernel(float* __restrict__ X, const GT* __restrict__ G, int64_t ldx, 
         const int64_t left = P - start;
         len = left < kTileCols ? static_cast<int32_t>(left) : kTileCols;
     }
+    if (kHasV) ex.v += start;
+    if (kHasS) ex.s += start;
     const int first = packed_byte(part.off, static_cast<int>(group_id));
     const int n = packed_byte(part.off, static_cast<int>(group_id) + 1) - first;
     if (len == kTileCols)
-        sync_tile<GT, kVpl, true>(X + start, G + start, len, ldx, ldg, part, first, n, lr);
+        sync_tile<GT, kVpl, true, kOpt, kHasV, kHasS>(X + start, G + start, len, ldx, ldg, ex, part, first, n, lr);
     else
-        sync_tile<GT, kVpl, false>(X + start, G + start, len, ldx, ldg, part, first, n, lr);
+        sync_tile<GT, kVpl, false, kOpt, kHasV, kHasS>(X + start, G + start, len, ldx, ldg, ex, part, first, n, lr);
 }
 
 struct SegmentScan {
@@ -252,9 +332,9 @@ int check_stacks(const void* X, const void* G, int32_t g_dtype, int64_t ldx, int
 // 2 * members-per-round * vpl = kSyncLoadsPerLane loads in flight per lane.
 int pick_vpl(int32_t largest) { return largest >= 8 ? 1 : largest >= 4 ? 2 : largest >= 2 ? 4 : 8; }
 
-template <typename GT, bool kRagged, int kVpl>
+template <typename GT, bool kRagged, int kVpl, bool kOpt, bool kHasV, bool kHasS>
 void launch_one(float* X, const GT* G, int64_t P, int64_t ldx, int64_t ldg, int64_t n_units, const Tile* tiles,
-                const PartitionArg& part, int32_t n_groups, float lr, hipStream_t st) {
+                const PartitionArg& part, int32_t n_groups, float lr, const Extras& ex, hipStream_t st) {
     // n_units: flat -> columns; ragged -> plan entries
     constexpr int kTileCols = kSyncThreads * 4 * kVpl;
     const int64_t n_tiles = kRagged ? n_units * (kPlanTileCols / kTileCols) : (n_units + kTileCols - 1) / kTileCols;
@@ -262,33 +342,124 @@ void launch_one(float* X, const GT* G, int64_t P, int64_t ldx, int64_t ldg, int6
     // the cap on wavefronts per CU pays off for HBM-sized work; a launch that fits the
     // chip in one go (cache-resident, latency-bound) is better off without it
     const unsigned lds_pad = n_tiles * n_groups <= kUncappedWorkgroups ? 0u : kSyncLdsPad;
-    hipLaunchKernelGGL((group_sync_kernel<GT, kRagged, kVpl>), grid, dim3(kSyncThreads, 1, 1), lds_pad, st, X, G,
-                       ldx, ldg, P, tiles, part, lr);
+    hipLaunchKernelGGL((group_sync_kernel<GT, kRagged, kVpl, kOpt, kHasV, kHasS>), grid, dim3(kSyncThreads, 1, 1),
+                       lds_pad, st, X, G, ldx, ldg, P, tiles, part, lr, ex);
+}
+
+template <typename GT, bool kRagged, bool kOpt, bool kHasV, bool kHasS>
+void launch_vpl(int vpl, float* X, const GT* G, int64_t P, int64_t ldx, int64_t ldg, int64_t n_units,
+                const Tile* tiles, const PartitionArg& part, int32_t n_groups, float lr, const Extras& ex,
+                hipStream_t st) {
+    switch (vpl) {
+        case 1: launch_one<GT, kRagged, 1, kOpt, kHasV, kHasS>(X, G, P, ldx, ldg, n_units, tiles, part, n_groups, lr, ex, st); break;
+        case 2: launch_one<GT, kRagged, 2, kOpt, kHasV, kHasS>(X, G, P, ldx, ldg, n_units, tiles, part, n_groups, lr, ex, st); break;
+        case 4: launch_one<GT, kRagged, 4, kOpt, kHasV, kHasS>(X, G, P, ldx, ldg, n_units, tiles, part, n_groups, lr, ex, st); break;
+        default: launch_one<GT, kRagged, 8, kOpt, kHasV, kHasS>(X, G, P, ldx, ldg, n_units, tiles, part, n_groups, lr, ex, st); break;
+    }
 }
 
 template <typename GT, bool kRagged>
-void launch_vpl(int vpl, float* X, const GT* G, int64_t P, int64_t ldx, int64_t ldg, int64_t n_units,
-                const Tile* tiles, const PartitionArg& part, int32_t n_groups, float lr, hipStream_t st) {
-    switch (vpl) {
-        case 1: launch_one<GT, kRagged, 1>(X, G, P, ldx, ldg, n_units, tiles, part, n_groups, lr, st); break;
-        case 2: launch_one<GT, kRagged, 2>(X, G, P, ldx, ldg, n_units, tiles, part, n_groups, lr, st); break;
-        case 4: launch_one<GT, kRagged, 4>(X, G, P, ldx, ldg, n_units, tiles, part, n_groups, lr, st); break;
-        default: launch_one<GT, kRagged, 8>(X, G, P, ldx, ldg, n_units, tiles, part, n_groups, lr, st); break;
-    }
+void launch_state(int vpl, float* X, const GT* G, int64_t P, int64_t ldx, int64_t ldg, int64_t n_units,
+                  const Tile* tiles, const PartitionArg& part, int32_t n_groups, float lr, bool opt, const Extras& ex,
+                  hipStream_t st) {
+    const bool has_v = ex.v != nullptr, has_s = ex.s != nullptr;
+    if (!opt)
+        launch_vpl<GT, kRagged, false, false, false>(vpl, X, G, P, ldx, ldg, n_units, tiles, part, n_groups, lr, ex, st);
+    else if (has_v && has_s)
+        launch_vpl<GT, kRagged, true, true, true>(vpl, X, G, P, ldx, ldg, n_units, tiles, part, n_groups, lr, ex, st);
+    else if (has_v)
+        launch_vpl<GT, kRagged, true, true, false>(vpl, X, G, P, ldx, ldg, n_units, tiles, part, n_groups, lr, ex, st);
+    else if (has_s)
+        launch_vpl<GT, kRagged, true, false, true>(vpl, X, G, P, ldx, ldg, n_units, tiles, part, n_groups, lr, ex, st);
+    else
+        launch_vpl<GT, kRagged, true, false, false>(vpl, X, G, P, ldx, ldg, n_units, tiles, part, n_groups, lr, ex, st);
 }
 
 template <bool kRagged>
 int launch(void* X, const void* G, int32_t g_dtype, int64_t P, int64_t ldx, int64_t ldg, int64_t n_units,
-           const Tile* tiles, const PartitionArg& part, int32_t largest, int32_t n_groups, float lr, void* stream) {
+           const Tile* tiles, const PartitionArg& part, int32_t largest, int32_t n_groups, float lr, bool opt,
+           const Extras& ex, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int vpl = pick_vpl(largest);
     if (g_dtype == DS_F32)
-        launch_vpl<float, kRagged>(vpl, static_cast<float*>(X), static_cast<const float*>(G), P, ldx, ldg, n_units,
-                                   tiles, part, n_groups, lr, st);
+        launch_state<float, kRagged>(vpl, static_cast<float*>(X), static_cast<const float*>(G), P, ldx, ldg, n_units,
+                                     tiles, part, n_groups, lr, opt, ex, st);
     else
-        launch_vpl<uint16_t, kRagged>(vpl, static_cast<float*>(X), static_cast<const uint16_t*>(G), P, ldx, ldg,
-                                      n_units, tiles, part, n_groups, lr, st);
+        launch_state<uint16_t, kRagged>(vpl, static_cast<float*>(X), static_cast<const uint16_t*>(G), P, ldx, ldg,
+                                        n_units, tiles, part, n_groups, lr, opt, ex, st);
     return hipGetLastError() == hipSuccess ? DS_OK : DS_ERR_HIP;
+}
+
+// Checks the optional state of the extended step and turns it into kernel arguments.
+// *opt_out says whether the extended arithmetic is needed at all.
+int read_opt(const ds_local_opt* opt, int64_t min_ld, Extras* ex, bool* opt_out) {
+    *ex = Extras{nullptr, nullptr, 0, 0, 0.f, 0.f, 0.f};
+    *opt_out = false;
+    if (!opt) return DS_OK;
+    if (opt->V) {
+        if (!ds::aligned16(opt->V) || opt->ldv % 4 != 0) return DS_ERR_ALIGN;
+        if (opt->ldv < min_ld) return DS_ERR_BAD_SHAPE;
+        ex->v = static_cast<float*>(opt->V);
+        ex->ldv = opt->ldv;
+        ex->momentum = opt->momentum;
+    }
+    if (opt->S) {
+        if (!ds::aligned16(opt->S) || opt->lds % 4 != 0) return DS_ERR_ALIGN;
+        if (opt->lds < min_ld) return DS_ERR_BAD_SHAPE;
+        ex->s = static_cast<float*>(opt->S);
+        ex->lds = opt->lds;
+        ex->factor = opt->swa_factor;
+    }
+    ex->weight_decay = opt->weight_decay;
+    *opt_out = opt->V || opt->S || opt->weight_decay != 0.f;
+    return DS_OK;
+}
+
+int64_t segments_end(const ds_segment* segs, int32_t S) {
+    int64_t end = 0;
+    for (int32_t s = 0; s < S; ++s) end = std::max(end, segs[s].offset + segs[s].length);
+    return end;
+}
+
+int group_sync_flat(void* X, const void* G, int32_t g_dtype, int64_t P, int64_t ldx, int64_t ldg, int32_t W,
+                    const int32_t* perm, const int32_t* off, int32_t n_groups, float lr, const ds_local_opt* opt,
+                    void* stream) {
+    int rc = check_stacks(X, G, g_dtype, ldx, ldg);
+    if (rc != DS_OK) return rc;
+    if (P < 0 || ldx < P || ldg < P) return DS_ERR_BAD_SHAPE;
+    Extras ex;
+    bool extended = false;
+    rc = read_opt(opt, P, &ex, &extended);
+    if (rc != DS_OK) return rc;
+    PartitionArg part;
+    int32_t max_size = 0, equal_size = 0;
+    rc = ds::pack_partition(W, perm, off, n_groups, &part, &max_size, &equal_size);
+    if (rc != DS_OK) return rc;
+    if (P / (kSyncThreads * 4) >= INT32_MAX) return DS_ERR_BAD_SHAPE;   // grid.x limit at the narrowest tile
+    if (P == 0) return DS_OK;
+    return launch<false>(X, G, g_dtype, P, ldx, ldg, P, nullptr, part, max_size, n_groups, lr, extended, ex, stream);
+}
+
+int group_sync_ragged(void* X, const void* G, int32_t g_dtype, const ds_segment* segs, int32_t S, int64_t ldx,
+                      int64_t ldg, int32_t W, const int32_t* perm, const int32_t* off, int32_t n_groups, float lr,
+                      const ds_local_opt* opt, const void* plan, size_t plan_bytes, void* stream) {
+    int rc = check_stacks(X, G, g_dtype, ldx, ldg);
+    if (rc != DS_OK) return rc;
+    const SegmentScan sc = scan_segments(segs, S, ldx, ldg, true);
+    if (sc.status != DS_OK) return sc.status;
+    Extras ex;
+    bool extended = false;
+    rc = read_opt(opt, segments_end(segs, S), &ex, &extended);
+    if (rc != DS_OK) return rc;
+    PartitionArg part;
+    int32_t max_size = 0, equal_size = 0;
+    rc = ds::pack_partition(W, perm, off, n_groups, &part, &max_size, &equal_size);
+    if (rc != DS_OK) return rc;
+    if (sc.n_tiles == 0) return DS_OK;
+    if (!plan || !ds::aligned16(plan) || plan_bytes < static_cast<size_t>(sc.n_tiles) * sizeof(Tile))
+        return DS_ERR_WORKSPACE;
+    return launch<true>(X, G, g_dtype, 0, ldx, ldg, sc.n_tiles, static_cast<const Tile*>(plan), part, max_size,
+                        n_groups, lr, extended, ex, stream);
 }
 
 }  // namespace
@@ -296,16 +467,13 @@ int launch(void* X, const void* G, int32_t g_dtype, int64_t P, int64_t ldx, int6
 extern "C" int ds_group_sync(void* X, const void* G, int32_t g_dtype, int64_t P, int64_t ldx,
                              int64_t ldg, int32_t W, const int32_t* perm, const int32_t* off,
                              int32_t n_groups, float lr, void* stream) {
-    int rc = check_stacks(X, G, g_dtype, ldx, ldg);
-    if (rc != DS_OK) return rc;
-    if (P < 0 || ldx < P || ldg < P) return DS_ERR_BAD_SHAPE;
-    PartitionArg part;
-    int32_t max_size = 0, equal_size = 0;
-    rc = ds::pack_partition(W, perm, off, n_groups, &part, &max_size, &equal_size);
-    if (rc != DS_OK) return rc;
-    if (P / (kSyncThreads * 4) >= INT32_MAX) return DS_ERR_BAD_SHAPE;   // grid.x limit at the narrowest tile
-    if (P == 0) return DS_OK;
-    return launch<false>(X, G, g_dtype, P, ldx, ldg, P, nullptr, part, max_size, n_groups, lr, stream);
+    return group_sync_flat(X, G, g_dtype, P, ldx, ldg, W, perm, off, n_groups, lr, nullptr, stream);
+}
+
+extern "C" int ds_group_sync_opt(void* X, const void* G, int32_t g_dtype, int64_t P, int64_t ldx,
+                                 int64_t ldg, int32_t W, const int32_t* perm, const int32_t* off,
+                                 int32_t n_groups, float lr, const ds_local_opt* opt, void* stream) {
+    return group_sync_flat(X, G, g_dtype, P, ldx, ldg, W, perm, off, n_groups, lr, opt, stream);
 }
 
 extern "C" size_t ds_ragged_plan_bytes(const ds_segment* segs, int32_t S) {
@@ -344,17 +512,14 @@ extern "C" int ds_group_sync_ragged(void* X, const void* G, int32_t g_dtype, con
                                     int32_t S, int64_t ldx, int64_t ldg, int32_t W, const int32_t* perm,
                                     const int32_t* off, int32_t n_groups, float lr, const void* plan,
                                     size_t plan_bytes, void* stream) {
-    int rc = check_stacks(X, G, g_dtype, ldx, ldg);
-    if (rc != DS_OK) return rc;
-    const SegmentScan sc = scan_segments(segs, S, ldx, ldg, true);
-    if (sc.status != DS_OK) return sc.status;
-    PartitionArg part;
-    int32_t max_size = 0, equal_size = 0;
-    rc = ds::pack_partition(W, perm, off, n_groups, &part, &max_size, &equal_size);
-    if (rc != DS_OK) return rc;
-    if (sc.n_tiles == 0) return DS_OK;
-    if (!plan || !ds::aligned16(plan) || plan_bytes < static_cast<size_t>(sc.n_tiles) * sizeof(Tile))
-        return DS_ERR_WORKSPACE;
-    return launch<true>(X, G, g_dtype, 0, ldx, ldg, sc.n_tiles, static_cast<const Tile*>(plan), part, max_size,
-                        n_groups, lr, stream);
+    return group_sync_ragged(X, G, g_dtype, segs, S, ldx, ldg, W, perm, off, n_groups, lr, nullptr, plan, plan_bytes,
+                             stream);
+}
+
+extern "C" int ds_group_sync_ragged_opt(void* X, const void* G, int32_t g_dtype, const ds_segment* segs,
+                                        int32_t S, int64_t ldx, int64_t ldg, int32_t W, const int32_t* perm,
+                                        const int32_t* off, int32_t n_groups, float lr, const ds_local_opt* opt,
+                                        const void* plan, size_t plan_bytes, void* stream) {
+    return group_sync_ragged(X, G, g_dtype, segs, S, ldx, ldg, W, perm, off, n_groups, lr, opt, plan, plan_bytes,
+                             stream);
 }

@@ -234,3 +234,21 @@ def test_pattern_errors():
     with pytest.raises(ds.DsError) as e:
         ds.ds_pattern_period([0, 2], [0, 0, 0], [0, 0])
     assert e.value.status == -10
+
+
+def test_extended_step_argument_errors():
+    def status(opt, P=16, ld=16):
+        with pytest.raises(ds.DsError) as e:
+            ds.ds_group_sync_opt(A, B, 0, P, ld, ld, 8, PERM8, OFF8, 0.1, opt, stream=0)
+        return e.value.status
+    assert status(ds.local_opt(V=2 * B + 4, ldv=16)) == -6           # misaligned buffer
+    assert status(ds.local_opt(V=2 * B, ldv=18)) == -6               # pitch not a multiple of 4
+    assert status(ds.local_opt(V=2 * B, ldv=12)) == -5               # pitch below P
+    assert status(ds.local_opt(S=2 * B, lds=8)) == -5
+    assert status(ds.local_opt(S=2 * B + 8, lds=16)) == -6
+    # nothing to do: P == 0 succeeds without a device
+    ds.ds_group_sync_opt(A, B, 0, 0, 16, 16, 8, PERM8, OFF8, 0.1, ds.local_opt(V=2 * B, ldv=16), stream=0)
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_group_sync_ragged_opt(A, B, 1, [(0, 64)], 4096, 4096, 8, PERM8, OFF8, 0.1,
+                                    ds.local_opt(V=2 * B, ldv=32), A, 1 << 20, stream=0)
+    assert e.value.status == -5                                      # buffer pitch ends before the segment
