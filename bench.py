@@ -83,6 +83,9 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=3,
                     help="benchmark configuration 1-5 (default 3, the one the headline metric is quoted on)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--local-opt", choices=["none", "momentum", "swa", "both"], default="none",
+                    help="time the extended step (momentum 0.9 / weight decay 5e-4 buffers and/or the SWA "
+                         "moving average, +8 B per worker-column each) instead of the plain one")
     ap.add_argument("--dense-rows", action="store_true",
                     help="leading dimension = P (rows not 256-byte aligned) instead of P rounded up to 64")
     ap.add_argument("--probe-copy", type=int, default=0, metavar="N",
@@ -118,6 +121,11 @@ def main() -> int:
     g_bytes = 2 if cfg.bf16_grads else 4
     run = wl.Run(cfg, dev, P=ld, ld=ld)
     X = run.init_params()
+    use_v = args.local_opt in ("momentum", "both")
+    use_s = args.local_opt in ("swa", "both")
+    V = torch.zeros_like(X) if use_v else None
+    S = X.clone() if use_s else None
+    opt = ds.local_opt(V, ld, 0.9, 5e-4 if use_v else 0.0, S, ld, 0.9) if (use_v or use_s) else None
     n_grad = 2                                   # gradient stacks resident in HBM, used in turn
     Gs = [run.gradients() for _ in range(n_grad)]
     P_cons = ld if cfg.ragged else P              # ragged: the norm runs over the whole arena
@@ -131,10 +139,10 @@ def main() -> int:
         if ev:
             ev[0].record(stream)
         if cfg.ragged:
-            ds.ds_group_sync_ragged(X, Gs[t % n_grad], ds.DS_BF16, packed, ld, ld, W, perm, off, cfg.lr,
-                                    plan, plan_bytes, stream)
+            ds.ds_group_sync_ragged_opt(X, Gs[t % n_grad], ds.DS_BF16, packed, ld, ld, W, perm, off, cfg.lr, opt,
+                                        plan, plan_bytes, stream)
         else:
-            ds.ds_group_sync(X, Gs[t % n_grad], ds.DS_F32, P, ld, ld, W, perm, off, cfg.lr, stream)
+            ds.ds_group_sync_opt(X, Gs[t % n_grad], ds.DS_F32, P, ld, ld, W, perm, off, cfg.lr, opt, stream)
         if ev:
             ev[1].record(stream)
         ds.ds_consensus(X, P_cons, ld, W, dev_out, ws, ws_bytes, stream)
@@ -170,7 +178,7 @@ def main() -> int:
     ms_step = (t1 - t0) / args.steps * 1e3
     sync_ms = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps
     cons_ms = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
-    sync_bytes = (8.0 + g_bytes) * W * P
+    sync_bytes = (8.0 + g_bytes + 8.0 * use_v + 8.0 * use_s) * W * P
     cons_bytes = 4.0 * W * P_cons
     sync_gbps = sync_bytes / (sync_ms * 1e-3) / 1e9
     cons_gbps = cons_bytes / (cons_ms * 1e-3) / 1e9
@@ -206,10 +214,14 @@ def main() -> int:
     }
     if probe is not None:
         out["probe_copy"] = probe
+    if opt is not None:
+        out["config"]["local_opt"] = args.local_opt
+        out["roofline"]["kernel"] += " + " + args.local_opt
+        out["roofline"]["traffic"] = None
     if cfg.ragged:
         out["dtype"] = "f32 (bf16 gradients)"
         out["roofline"]["kernel"] = "group_sync_kernel<bf16, ragged>"
-    if not args.no_cpu_baseline and not cfg.ragged:
+    if not args.no_cpu_baseline and not cfg.ragged and opt is None:
         out["cpu_baseline"] = cpu_baseline(cfg, X, Gs[0], iters=8)
     print(json.dumps(out), flush=True)
     return 0
