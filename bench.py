@@ -86,6 +86,10 @@ def main() -> int:
     ap.add_argument("--local-opt", choices=["none", "momentum", "swa", "both"], default="none",
                     help="time the extended step (momentum 0.9 / weight decay 5e-4 buffers and/or the SWA "
                          "moving average, +8 B per worker-column each) instead of the plain one")
+    ap.add_argument("--layerwise", type=int, default=0, metavar="K",
+                    help="configuration 5 only: synchronise layer by layer, one launch per segment in reverse "
+                         "layer order, round-robin over K streams with one event per layer (the shape of the "
+                         "paper's backward-hook / pre-forward-hook overlap) instead of the single ragged launch")
     ap.add_argument("--dense-rows", action="store_true",
                     help="leading dimension = P (rows not 256-byte aligned) instead of P rounded up to 64")
     ap.add_argument("--probe-copy", type=int, default=0, metavar="N",
@@ -134,11 +138,37 @@ def main() -> int:
     dev_out = torch.zeros(W, dtype=torch.float64, device=dev)
     stream = torch.cuda.current_stream()
 
+    side = [torch.cuda.Stream() for _ in range(args.layerwise)] if args.layerwise > 0 else []
+    if side and not cfg.ragged:
+        print("bench.py: --layerwise needs --config 5", file=sys.stderr)
+        return 2
+    layer_done = [torch.cuda.Event() for _ in segs] if side else []
+
+    def layerwise(t, perm, off):
+        # Sec. V-A1: the backward hook of a layer updates it locally and starts its synchronisation
+        # without blocking; the pre-forward hook waits for that layer's event.  Layers become ready
+        # from the last to the first; here all are ready at once and the main stream waits for all.
+        fork = torch.cuda.Event()
+        fork.record(stream)
+        for st in side:
+            st.wait_event(fork)
+        G = Gs[t % n_grad]
+        for k, s in enumerate(reversed(range(len(segs)))):
+            o, n = segs[s]
+            st = side[k % len(side)]
+            ds.ds_group_sync_opt(X.data_ptr() + 4 * o, G.data_ptr() + g_bytes * o, ds.DS_BF16, n, ld, ld, W,
+                                 perm, off, cfg.lr, None, st)
+            layer_done[s].record(st)
+        for e in layer_done:
+            stream.wait_event(e)
+
     def step(t, ev=None):
         perm, off = ds.ds_partition(cfg.seed, t, W, cfg.sizes)
         if ev:
             ev[0].record(stream)
-        if cfg.ragged:
+        if side:
+            layerwise(t, perm, off)
+        elif cfg.ragged:
             ds.ds_group_sync_ragged_opt(X, Gs[t % n_grad], ds.DS_BF16, packed, ld, ld, W, perm, off, cfg.lr, opt,
                                         plan, plan_bytes, stream)
         else:
@@ -218,6 +248,9 @@ def main() -> int:
         out["config"]["local_opt"] = args.local_opt
         out["roofline"]["kernel"] += " + " + args.local_opt
         out["roofline"]["traffic"] = None
+    if side:
+        out["config"]["layerwise_streams"] = len(side)
+        out["config"]["launches_per_step"] = len(segs)
     if cfg.ragged:
         out["dtype"] = "f32 (bf16 gradients)"
         out["roofline"]["kernel"] = "group_sync_kernel<bf16, ragged>"

@@ -309,3 +309,24 @@ def test_topology_pattern_drives_the_gpu_step():
             ds.ds_group_sync(X, Z, ds.DS_F32, P, ld, ld, W, perm, off, 0.0)
         d = gpu_consensus(X, P, ld, W)
         assert np.all(d**2 <= sigma**(2 * k) * fro2 * (1 + 1e-5) + 1e-9)
+
+
+def test_layer_by_layer_launches_equal_the_ragged_launch():
+    # Sec. V-A1: one synchronisation per layer; here one launch per segment on a view of the stacks
+    W, sizes = 8, [4, 4]
+    segs = [(0, 300), (320, 2047), (2368, 2049), (4424, 5), (4480, 1025), (5512, 70000)]
+    ld = 75520
+    X, G = random_stacks(95, W, ld, ld, True)
+    X2 = X.clone()
+    perm, off = ds.ds_partition(6, 0, W, sizes)
+    nbytes = ds.ds_ragged_plan_bytes(segs)
+    plan = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    ds.ds_ragged_plan(segs, ld, ld, plan, nbytes)
+    ds.ds_group_sync_ragged(X, G, ds.DS_BF16, segs, ld, ld, W, perm, off, 0.01, plan, nbytes)
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    torch.cuda.synchronize()
+    for k, (o, n) in enumerate(reversed(segs)):
+        ds.ds_group_sync(X2.data_ptr() + 4 * o, G.data_ptr() + 2 * o, ds.DS_BF16, n, ld, ld, W, perm, off, 0.01,
+                         streams[k % 3])
+    torch.cuda.synchronize()
+    assert torch.equal(X, X2)
