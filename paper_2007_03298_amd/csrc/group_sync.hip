@@ -52,11 +52,11 @@ using ds::Tile;
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-// Dynamic LDS requested per workgroup (never touched): 160 KiB / 32 KiB = 5 workgroups per CU.
-#ifndef DS_SYNC_LDS_PAD
-#define DS_SYNC_LDS_PAD 32768
-#endif
-constexpr unsigned kSyncLdsPad = DS_SYNC_LDS_PAD;
+// Dynamic LDS requested per workgroup (never touched): 160 KiB / 32 KiB = 5 wavefronts
+// per CU for the plain step; the extended step moves half as much again per wavefront
+// and does best with 3 per CU (160 / 52).
+constexpr unsigned kSyncLdsPad = 32768;
+constexpr unsigned kSyncLdsPadState = 53248;
 constexpr int64_t kUncappedWorkgroups = 256 * 32;   // one full-occupancy load of the 256 CUs
 
 template <typename V>
@@ -341,7 +341,8 @@ void launch_one(float* X, const GT* G, int64_t P, int64_t ldx, int64_t ldg, int6
     const dim3 grid(static_cast<uint32_t>(n_tiles), static_cast<uint32_t>(n_groups), 1);
     // the cap on wavefronts per CU pays off for HBM-sized work; a launch that fits the
     // chip in one go (cache-resident, latency-bound) is better off without it
-    const unsigned lds_pad = n_tiles * n_groups <= kUncappedWorkgroups ? 0u : kSyncLdsPad;
+    const unsigned lds_pad =
+        n_tiles * n_groups <= kUncappedWorkgroups ? 0u : ((kHasV || kHasS) ? kSyncLdsPadState : kSyncLdsPad);
     hipLaunchKernelGGL((group_sync_kernel<GT, kRagged, kVpl, kOpt, kHasV, kHasS>), grid, dim3(kSyncThreads, 1, 1),
                        lds_pad, st, X, G, ldx, ldg, P, tiles, part, lr, ex);
 }
