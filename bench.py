@@ -205,6 +205,20 @@ def main() -> int:
     torch.cuda.synchronize()
     t1 = time.perf_counter()
 
+    # reported separately, never part of `value`: the norm from one row per group, valid because the
+    # step has just made the members of every group identical
+    perm, off = ds.ds_partition(cfg.seed, args.warmup + args.steps - 1, W, cfg.sizes)
+    ge = [torch.cuda.Event(enable_timing=True) for _ in range(11)]
+    dev_grouped = torch.zeros(W, dtype=torch.float64, device=dev)
+    ds.ds_consensus_grouped(X, P_cons, ld, W, perm, off, dev_grouped, ws, ws_bytes, stream)
+    ge[0].record(stream)
+    for k in range(10):
+        ds.ds_consensus_grouped(X, P_cons, ld, W, perm, off, dev_grouped, ws, ws_bytes, stream)
+        ge[k + 1].record(stream)
+    torch.cuda.synchronize()
+    grouped_ms = sum(ge[k].elapsed_time(ge[k + 1]) for k in range(10)) / 10
+    grouped_gap = float((dev_grouped - dev_out).abs().max() / dev_out.abs().max().clamp_min(1e-300))
+
     ms_step = (t1 - t0) / args.steps * 1e3
     sync_ms = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps
     cons_ms = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
@@ -236,6 +250,9 @@ def main() -> int:
         "consensus": {"ms": round(cons_ms, 4), "GBps": round(cons_gbps, 1),
                       "pct_of_hbm_peak": round(100.0 * cons_gbps / HBM_PEAK_GBPS, 2),
                       "max_deviation": float(d.max())},
+        "consensus_grouped": {"ms": round(grouped_ms, 4), "bytes_read": int(4.0 * len(cfg.sizes) * P_cons),
+                              "note": "one row per group; valid right after a group-sync; not in value",
+                              "max_rel_gap_to_full": grouped_gap},
         "roofline": {"bound": "hbm", "kernel": "group_sync_kernel<float, flat>", "bytes_per_launch": int(sync_bytes),
                      "achieved": round(sync_gbps, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(sync_gbps / HBM_PEAK_GBPS, 4),

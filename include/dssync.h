@@ -271,6 +271,22 @@ int ds_consensus(const void* X, int64_t P, int64_t ld, int32_t W, double* dev_ou
                  size_t workspace_bytes, void* stream);
 
 /*
+ * ds_consensus_grouped -- the same norms for a stack whose rows are known to be
+ * identical inside every group of the given division, which is the state
+ * right after ds_group_sync* with that division (Listing 1: members leave
+ * Average with the same model).  Only one row per group is read
+ * (4*n_groups*P bytes instead of 4*W*P); with m_k that row and n_k = |g_k|:
+ *     xbar[p] = (1/W) * sum_k n_k * m_k[p];   dev_out[i] = || m_{g(i)} - xbar ||_2
+ * PRECONDITION, not checked: rows of a group are equal.  If they are not, the
+ * result describes the stack in which every member is replaced by its group's
+ * first member.  Arguments, workspace and errors as ds_consensus, plus those
+ * of a division (DS_ERR_BAD_SIZES, DS_ERR_BAD_PART).
+ */
+int ds_consensus_grouped(const void* X, int64_t P, int64_t ld, int32_t W, const int32_t* perm,
+                         const int32_t* off, int32_t n_groups, double* dev_out, void* workspace,
+                         size_t workspace_bytes, void* stream);
+
+/*
  * ds_probe_copy -- measurement aid, not a step of the method: a plain
  * device-to-device streaming copy of `bytes` bytes (reads `bytes`, writes
  * `bytes`).  The benchmark uses it as the attainable-bandwidth yardstick and

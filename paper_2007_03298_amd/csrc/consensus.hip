@@ -41,24 +41,43 @@ __host__ __device__ constexpr int padded_w(int W) { return W <= 8 ? 8 : W <= 16 
 // 256 CUs busy without a long tail (2048 and 8192 measured 1-4 % slower).
 constexpr int kTargetBlocks = 4096;
 
+// Which rows of the stack stand for what.  Plain consensus: every worker's own
+// row, weight 1.  Grouped consensus (rows of a group are known to be
+// identical, as they are right after a group-sync): one row per group, weight
+// = group size, and `src` says which group's total each worker receives.
+// One byte per entry, four per 32-bit word, read with scalar loads.
+struct RowTable {
+    uint32_t row[DS_MAX_W / 4];
+    uint32_t weight[DS_MAX_W / 4];
+    uint32_t src[DS_MAX_W / 4];
+};
+
+__device__ __forceinline__ int table_byte(const uint32_t* words, int i) {
+    return static_cast<int>((words[i >> 2] >> ((i & 3) * 8)) & 0xffu);
+}
+
 // Adds one tile's squared deviations to the lane accumulators.  kFull: every
 // lane's kVec columns lie inside the row (no predicates, so the W loads issue
 // back to back).
-template <int kWPad, int kVec, bool kFull>
+// n_rows rows take part; kGrouped: row i is tab.row[i] with weight tab.weight[i]
+// and total_weight = number of workers, else row i with weight 1.
+template <int kWPad, int kVec, bool kFull, bool kGrouped>
 __device__ __forceinline__ void consensus_tile(float (&acc)[kWPad], const float* __restrict__ X, int64_t c,
-                                               int64_t P, int64_t ld, int W) {
+                                               int64_t P, int64_t ld, int W, const RowTable& tab,
+                                               int total_weight) {
     typedef typename VecOf<kVec>::type vec_t;
     vec_t row[kWPad];
 #pragma unroll
     for (int i = 0; i < kWPad; ++i) {
         if (i < W) {
+            const int64_t r = kGrouped ? table_byte(tab.row, i) : i;
             if (kFull) {
-                row[i] = __builtin_nontemporal_load(reinterpret_cast<const vec_t*>(X + i * ld + c));
+                row[i] = __builtin_nontemporal_load(reinterpret_cast<const vec_t*>(X + r * ld + c));
             } else {
                 // last, partial vector of the row: columns at or beyond P count as 0
                 // in every row, which adds nothing to any deviation
 #pragma unroll
-                for (int e = 0; e < kVec; ++e) row[i][e] = (c + e < P) ? X[i * ld + c + e] : 0.f;
+                for (int e = 0; e < kVec; ++e) row[i][e] = (c + e < P) ? X[r * ld + c + e] : 0.f;
             }
         }
     }
@@ -68,14 +87,16 @@ __device__ __forceinline__ void consensus_tile(float (&acc)[kWPad], const float*
 #pragma unroll
     for (int i = 0; i < kWPad; ++i) {
         if (i < W) {
+            const double w = kGrouped ? static_cast<double>(table_byte(tab.weight, i)) : 1.0;
 #pragma unroll
-            for (int e = 0; e < kVec; ++e) mean[e] += static_cast<double>(row[i][e]);
+            for (int e = 0; e < kVec; ++e)
+                mean[e] += kGrouped ? w * static_cast<double>(row[i][e]) : static_cast<double>(row[i][e]);
         }
     }
     // mean as an unevaluated fp32 pair hi + lo (|lo| <= ulp(hi)/2): subtracting
     // hi, then lo, in fp32 leaves an error that is relative to the difference
     // itself, and is exactly 0 when every row equals the mean
-    const double wd = static_cast<double>(W);
+    const double wd = static_cast<double>(kGrouped ? total_weight : W);
     float hi[kVec], lo[kVec];
 #pragma unroll
     for (int e = 0; e < kVec; ++e) {
@@ -95,10 +116,10 @@ __device__ __forceinline__ void consensus_tile(float (&acc)[kWPad], const float*
     }
 }
 
-template <int kWPad, int kVec>
+template <int kWPad, int kVec, bool kGrouped>
 __global__ void __launch_bounds__(kThreads)
 consensus_partial_kernel(const float* __restrict__ X, int64_t P, int64_t ld, int W, int tiles_per_block,
-                         double* __restrict__ partial) {
+                         double* __restrict__ partial, RowTable tab, int total_weight) {
     constexpr int kTileCols = kThreads * kVec;
     float acc[kWPad];
 #pragma unroll
@@ -111,12 +132,12 @@ consensus_partial_kernel(const float* __restrict__ X, int64_t P, int64_t ld, int
     for (int64_t tile = tile0; tile < tile1; ++tile) {
         const int64_t c = tile * kTileCols + static_cast<int64_t>(threadIdx.x) * kVec;
         if ((tile + 1) * kTileCols <= P) {
-            consensus_tile<kWPad, kVec, true>(acc, X, c, P, ld, W);
+            consensus_tile<kWPad, kVec, true, kGrouped>(acc, X, c, P, ld, W, tab, total_weight);
         } else if (c < P) {
             if (c + kVec <= P)
-                consensus_tile<kWPad, kVec, true>(acc, X, c, P, ld, W);
+                consensus_tile<kWPad, kVec, true, kGrouped>(acc, X, c, P, ld, W, tab, total_weight);
             else
-                consensus_tile<kWPad, kVec, false>(acc, X, c, P, ld, W);
+                consensus_tile<kWPad, kVec, false, kGrouped>(acc, X, c, P, ld, W, tab, total_weight);
         }
     }
 
@@ -140,11 +161,12 @@ consensus_partial_kernel(const float* __restrict__ X, int64_t P, int64_t ld, int
     }
 }
 
-// one workgroup per worker: fixed-order sum of its column of the partial rows
+// one workgroup per worker: fixed-order sum of its column (tab.src) of the partial rows
 __global__ void __launch_bounds__(kThreads)
-consensus_final_kernel(const double* __restrict__ partial, int n_rows, int w_pad, double* __restrict__ out) {
+consensus_final_kernel(const double* __restrict__ partial, int n_rows, int w_pad, double* __restrict__ out,
+                       RowTable tab) {
     __shared__ double buf[kThreads];
-    const int i = blockIdx.x;
+    const int i = table_byte(tab.src, static_cast<int>(blockIdx.x));
     double v = 0.0;
     for (int b = threadIdx.x; b < n_rows; b += kThreads) v += partial[static_cast<int64_t>(b) * w_pad + i];
     buf[threadIdx.x] = v;
@@ -153,7 +175,7 @@ consensus_final_kernel(const double* __restrict__ partial, int n_rows, int w_pad
         if (static_cast<int>(threadIdx.x) < half) buf[threadIdx.x] += buf[threadIdx.x + half];
         __syncthreads();
     }
-    if (threadIdx.x == 0) out[i] = sqrt(buf[0]);
+    if (threadIdx.x == 0) out[blockIdx.x] = sqrt(buf[0]);
 }
 
 }  // namespace
@@ -163,16 +185,15 @@ extern "C" size_t ds_consensus_workspace_bytes(int32_t W, int64_t P) {
     return static_cast<size_t>(kMaxBlocks) * static_cast<size_t>(padded_w(W)) * sizeof(double);
 }
 
-extern "C" int ds_consensus(const void* X, int64_t P, int64_t ld, int32_t W, double* dev_out,
-                            void* workspace, size_t workspace_bytes, void* stream) {
-    if (!X || !dev_out) return DS_ERR_NULL;
-    if (W < 1 || W > DS_MAX_W) return DS_ERR_BAD_W;
-    if (P < 0 || ld < P) return DS_ERR_BAD_SHAPE;
-    if (!ds::aligned16(X) || ld % 4 != 0 || (reinterpret_cast<uintptr_t>(dev_out) & 7u) != 0) return DS_ERR_ALIGN;
-    if (!workspace || !ds::aligned16(workspace) || workspace_bytes < ds_consensus_workspace_bytes(W, P))
-        return DS_ERR_WORKSPACE;
+namespace {
 
-    const int w_pad = padded_w(W);
+void set_byte(uint32_t* words, int i, int value) { words[i >> 2] |= static_cast<uint32_t>(value) << ((i & 3) * 8); }
+
+// n_rows rows are read (W for the plain norm, n_groups for the grouped one); W outputs.
+template <bool kGrouped>
+int launch_consensus(const float* x, int64_t P, int64_t ld, int32_t W, int32_t n_rows, const RowTable& tab,
+                     double* dev_out, double* partial, hipStream_t st) {
+    const int w_pad = padded_w(n_rows);
     const int vec = w_pad == 64 ? 2 : 4;
     const int64_t tile_cols = static_cast<int64_t>(kThreads) * vec;
     const int64_t n_tiles = (P + tile_cols - 1) / tile_cols;
@@ -186,18 +207,57 @@ extern "C" int ds_consensus(const void* X, int64_t P, int64_t ld, int32_t W, dou
     const int64_t want_blocks = (n_tiles + per_block - 1) / per_block;
     const int n_blocks = static_cast<int>(want_blocks < 1 ? 1 : want_blocks);
     const int tpb = static_cast<int>(per_block);
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    const float* x = static_cast<const float*>(X);
-    double* partial = static_cast<double*>(workspace);
     const dim3 grid(static_cast<uint32_t>(n_blocks)), block(kThreads);
     switch (w_pad) {
-        case 8: hipLaunchKernelGGL((consensus_partial_kernel<8, 4>), grid, block, 0, st, x, P, ld, W, tpb, partial); break;
-        case 16: hipLaunchKernelGGL((consensus_partial_kernel<16, 4>), grid, block, 0, st, x, P, ld, W, tpb, partial); break;
-        case 32: hipLaunchKernelGGL((consensus_partial_kernel<32, 4>), grid, block, 0, st, x, P, ld, W, tpb, partial); break;
-        default: hipLaunchKernelGGL((consensus_partial_kernel<64, 2>), grid, block, 0, st, x, P, ld, W, tpb, partial); break;
+        case 8: hipLaunchKernelGGL((consensus_partial_kernel<8, 4, kGrouped>), grid, block, 0, st, x, P, ld, n_rows, tpb, partial, tab, W); break;
+        case 16: hipLaunchKernelGGL((consensus_partial_kernel<16, 4, kGrouped>), grid, block, 0, st, x, P, ld, n_rows, tpb, partial, tab, W); break;
+        case 32: hipLaunchKernelGGL((consensus_partial_kernel<32, 4, kGrouped>), grid, block, 0, st, x, P, ld, n_rows, tpb, partial, tab, W); break;
+        default: hipLaunchKernelGGL((consensus_partial_kernel<64, 2, kGrouped>), grid, block, 0, st, x, P, ld, n_rows, tpb, partial, tab, W); break;
     }
     if (hipGetLastError() != hipSuccess) return DS_ERR_HIP;
-    hipLaunchKernelGGL(consensus_final_kernel, dim3(static_cast<uint32_t>(W)), block, 0, st, partial, n_blocks,
-                       w_pad, dev_out);
+    hipLaunchKernelGGL(consensus_final_kernel, dim3(static_cast<uint32_t>(W)), block, 0, st, partial, n_blocks, w_pad,
+                       dev_out, tab);
     return hipGetLastError() == hipSuccess ? DS_OK : DS_ERR_HIP;
+}
+
+int check_consensus_args(const void* X, int64_t P, int64_t ld, int32_t W, const double* dev_out, const void* workspace,
+                         size_t workspace_bytes) {
+    if (!X || !dev_out) return DS_ERR_NULL;
+    if (W < 1 || W > DS_MAX_W) return DS_ERR_BAD_W;
+    if (P < 0 || ld < P) return DS_ERR_BAD_SHAPE;
+    if (!ds::aligned16(X) || ld % 4 != 0 || (reinterpret_cast<uintptr_t>(dev_out) & 7u) != 0) return DS_ERR_ALIGN;
+    if (!workspace || !ds::aligned16(workspace) || workspace_bytes < ds_consensus_workspace_bytes(W, P))
+        return DS_ERR_WORKSPACE;
+    return DS_OK;
+}
+
+}  // namespace
+
+extern "C" int ds_consensus(const void* X, int64_t P, int64_t ld, int32_t W, double* dev_out,
+                            void* workspace, size_t workspace_bytes, void* stream) {
+    const int rc = check_consensus_args(X, P, ld, W, dev_out, workspace, workspace_bytes);
+    if (rc != DS_OK) return rc;
+    RowTable tab = {};
+    for (int32_t i = 0; i < W; ++i) set_byte(tab.src, i, i);
+    return launch_consensus<false>(static_cast<const float*>(X), P, ld, W, W, tab, dev_out,
+                                   static_cast<double*>(workspace), static_cast<hipStream_t>(stream));
+}
+
+extern "C" int ds_consensus_grouped(const void* X, int64_t P, int64_t ld, int32_t W, const int32_t* perm,
+                                    const int32_t* off, int32_t n_groups, double* dev_out, void* workspace,
+                                    size_t workspace_bytes, void* stream) {
+    const int rc = check_consensus_args(X, P, ld, W, dev_out, workspace, workspace_bytes);
+    if (rc != DS_OK) return rc;
+    ds::PartitionArg packed;
+    int32_t max_size = 0, equal_size = 0;
+    const int prc = ds::pack_partition(W, perm, off, n_groups, &packed, &max_size, &equal_size);
+    if (prc != DS_OK) return prc;
+    RowTable tab = {};
+    for (int32_t k = 0; k < n_groups; ++k) {
+        set_byte(tab.row, k, perm[off[k]]);                 // the group's first member stands for all of them
+        set_byte(tab.weight, k, off[k + 1] - off[k]);
+        for (int32_t q = off[k]; q < off[k + 1]; ++q) set_byte(tab.src, perm[q], k);
+    }
+    return launch_consensus<true>(static_cast<const float*>(X), P, ld, W, n_groups, tab, dev_out,
+                                  static_cast<double*>(workspace), static_cast<hipStream_t>(stream));
 }

@@ -330,3 +330,47 @@ def test_layer_by_layer_launches_equal_the_ragged_launch():
                          streams[k % 3])
     torch.cuda.synchronize()
     assert torch.equal(X, X2)
+
+
+def gpu_consensus_grouped(X, P, ld, W, perm, off):
+    need = ds.ds_consensus_workspace_bytes(W, P)
+    ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+    out = torch.full((W,), -1.0, dtype=torch.float64, device=DEV)
+    ds.ds_consensus_grouped(X, P, ld, W, perm, off, out, ws, need)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+@pytest.mark.parametrize("W,sizes,P", [(8, [4, 4], 10001), (8, [2, 3, 3], 4097), (32, [8] * 4, 300001),
+                                      (64, [8] * 8, 20003), (64, [1] * 64, 5000), (16, [16], 3000),
+                                      (33, [11, 22], 1027)])
+def test_grouped_consensus_after_a_step(W, sizes, P):
+    # right after a step the members of a group are identical: one row per group is enough
+    ld = (P + 3) // 4 * 4
+    X, G = random_stacks(400 + W, W, ld, ld, False)
+    perm, off = ds.ds_partition(8, 3, W, sizes)
+    ds.ds_group_sync(X, G, ds.DS_F32, P, ld, ld, W, perm, off, 0.01)
+    got = gpu_consensus_grouped(X, P, ld, W, perm, off)
+    full = gpu_consensus(X, P, ld, W)
+    want = oracle.consensus(wl.tensor_to_numpy(X), P)
+    if len(sizes) == 1:
+        assert np.array_equal(got, np.zeros(W))
+    else:
+        np.testing.assert_allclose(got, want, rtol=1e-5)
+        np.testing.assert_allclose(got, full, rtol=1e-6)
+    # members of a group share one value
+    for k in range(len(off) - 1):
+        assert len({got[i] for i in perm[off[k]:off[k + 1]]}) == 1
+
+
+def test_grouped_consensus_describes_the_first_members_when_rows_differ():
+    # the documented behaviour off the precondition: every member counts as its group's first member
+    W, P, ld = 8, 3001, 3004
+    X, _ = random_stacks(450, W, ld, 4, False)
+    perm, off = ds.ds_partition(2, 0, W, [4, 4])
+    got = gpu_consensus_grouped(X, P, ld, W, perm, off)
+    Xr = wl.tensor_to_numpy(X).copy()
+    for k in range(2):
+        for i in perm[off[k]:off[k + 1]]:
+            Xr[i] = Xr[perm[off[k]]]
+    np.testing.assert_allclose(got, oracle.consensus(Xr, P), rtol=1e-5)

@@ -252,3 +252,20 @@ def test_extended_step_argument_errors():
         ds.ds_group_sync_ragged_opt(A, B, 1, [(0, 64)], 4096, 4096, 8, PERM8, OFF8, 0.1,
                                     ds.local_opt(V=2 * B, ldv=32), A, 1 << 20, stream=0)
     assert e.value.status == -5                                      # buffer pitch ends before the segment
+
+
+def test_grouped_consensus_argument_errors():
+    need = ds.ds_consensus_workspace_bytes(8, 100)
+
+    def status(perm=PERM8, off=OFF8, **kw):
+        args = dict(X=A, P=16, ld=16, W=8, out=B, ws=3 * B, ws_bytes=need)
+        args.update(kw)
+        with pytest.raises(ds.DsError) as e:
+            ds.ds_consensus_grouped(args["X"], args["P"], args["ld"], args["W"], perm, off, args["out"], args["ws"],
+                                    args["ws_bytes"], stream=0)
+        return e.value.status
+    assert status(X=0) == -1
+    assert status(P=17) == -5
+    assert status(ws_bytes=need - 1) == -8
+    assert status(perm=[0, 1, 2, 3, 4, 5, 6, 6]) == -4
+    assert status(off=[0, 4, 7]) == -4
