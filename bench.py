@@ -78,8 +78,9 @@ def cpu_baseline(cfg, X, G, iters: int):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=30,
+                    help="untimed steps first; the first ~25 steps after start-up run about 8 %% slower")
     ap.add_argument("--config", type=int, default=3,
                     help="benchmark configuration 1-5 (default 3, the one the headline metric is quoted on)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
