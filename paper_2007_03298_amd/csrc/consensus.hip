@@ -4,8 +4,8 @@
 // A read-only streaming pass, bound by HBM bandwidth (4 bytes per (worker,
 // column), a handful of ALU operations on them).  Mapping:
 //   - a lane loads its kVec consecutive columns of ALL W rows into registers
-//     (one 128-bit or 64-bit load per row, coalesced across the wavefront), so
-//     X is read exactly once;
+//     (one 128-bit load per row up to 16 rows, one 64-bit load per row above,
+//     coalesced across the wavefront), so X is read exactly once;
 //   - the column mean is formed in fp64 and split into an fp32 pair hi + lo;
 //     the difference (x_i - hi) - lo is then plain fp32 work whose rounding
 //     error is relative to the difference itself (and exactly zero for
@@ -194,7 +194,7 @@ template <bool kGrouped>
 int launch_consensus(const float* x, int64_t P, int64_t ld, int32_t W, int32_t n_rows, const RowTable& tab,
                      double* dev_out, double* partial, hipStream_t st) {
     const int w_pad = padded_w(n_rows);
-    const int vec = w_pad == 64 ? 2 : 4;
+    const int vec = w_pad >= 32 ? 2 : 4;   // keeps the rows of one lane within 64 registers
     const int64_t tile_cols = static_cast<int64_t>(kThreads) * vec;
     const int64_t n_tiles = (P + tile_cols - 1) / tile_cols;
     // consecutive tiles per workgroup: enough to amortise the end-of-block reduction,
@@ -211,7 +211,7 @@ int launch_consensus(const float* x, int64_t P, int64_t ld, int32_t W, int32_t n
     switch (w_pad) {
         case 8: hipLaunchKernelGGL((consensus_partial_kernel<8, 4, kGrouped>), grid, block, 0, st, x, P, ld, n_rows, tpb, partial, tab, W); break;
         case 16: hipLaunchKernelGGL((consensus_partial_kernel<16, 4, kGrouped>), grid, block, 0, st, x, P, ld, n_rows, tpb, partial, tab, W); break;
-        case 32: hipLaunchKernelGGL((consensus_partial_kernel<32, 4, kGrouped>), grid, block, 0, st, x, P, ld, n_rows, tpb, partial, tab, W); break;
+        case 32: hipLaunchKernelGGL((consensus_partial_kernel<32, 2, kGrouped>), grid, block, 0, st, x, P, ld, n_rows, tpb, partial, tab, W); break;
         default: hipLaunchKernelGGL((consensus_partial_kernel<64, 2, kGrouped>), grid, block, 0, st, x, P, ld, n_rows, tpb, partial, tab, W); break;
     }
     if (hipGetLastError() != hipSuccess) return DS_ERR_HIP;
