@@ -287,6 +287,22 @@ int ds_consensus_grouped(const void* X, int64_t P, int64_t ld, int32_t W, const 
                          size_t workspace_bytes, void* stream);
 
 /*
+ * ds_padded_ld -- the leading dimension (row pitch, in elements) the kernels
+ * run fastest with for rows of P elements: P rounded up to an odd multiple of
+ * 256.  Data layout only, not a step of the method (the paper stacks the
+ * replicas as the rows of X_k, Sec. IV-B2, and says nothing of a pitch).
+ * Every row of an fp32 stack then starts on a 1-KiB boundary, so each 1-KiB
+ * wavefront access covers one aligned KiB of its row (measured 2-5 % faster
+ * on MI355X than rows starting on other 256-byte boundaries, 15-20 % faster
+ * than a dense pitch whose rows straddle cache lines), and the odd multiple
+ * keeps the pitch away from large powers of two, where equal columns of
+ * different rows fall on the same memory channels.  Any ld >= P that is a
+ * multiple of 4 is accepted by every entry point; this one is a recommendation.
+ * Host only.  Returns 0 if P < 0 or the result would not fit in int64_t.
+ */
+int64_t ds_padded_ld(int64_t P);
+
+/*
  * ds_probe_copy -- measurement aid, not a step of the method: a plain
  * device-to-device streaming copy of `bytes` bytes (reads `bytes`, writes
  * `bytes`).  The benchmark uses it as the attainable-bandwidth yardstick and

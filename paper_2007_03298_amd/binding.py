@@ -21,7 +21,7 @@ DS_F32, DS_BF16 = 0, 1
 DS_MAX_W = 64
 
 EXPORTS = ("ds_status_string", "ds_partition", "ds_pattern", "ds_pattern_period", "ds_group_sync", "ds_ragged_plan_bytes", "ds_ragged_plan",
-           "ds_group_sync_ragged", "ds_group_sync_opt", "ds_group_sync_ragged_opt", "ds_consensus_workspace_bytes", "ds_consensus", "ds_consensus_grouped", "ds_probe_copy")
+           "ds_group_sync_ragged", "ds_group_sync_opt", "ds_group_sync_ragged_opt", "ds_consensus_workspace_bytes", "ds_consensus", "ds_consensus_grouped", "ds_probe_copy", "ds_padded_ld")
 
 
 class DsError(RuntimeError):
@@ -78,6 +78,8 @@ def _load() -> ctypes.CDLL:
     lib.ds_consensus.argtypes = [vp, i64, i64, i32, vp, vp, sz, vp]
     lib.ds_consensus_grouped.restype = ctypes.c_int
     lib.ds_consensus_grouped.argtypes = [vp, i64, i64, i32, i32p, i32p, i32, vp, vp, sz, vp]
+    lib.ds_padded_ld.restype = i64
+    lib.ds_padded_ld.argtypes = [i64]
     lib.ds_probe_copy.restype = ctypes.c_int
     lib.ds_probe_copy.argtypes = [vp, vp, sz, vp]
     return lib
@@ -258,6 +260,10 @@ def ds_consensus_grouped(X, P: int, ld: int, W: int, perm, off, dev_out, workspa
     perm, off = _i32(perm), _i32(off)
     _check(_lib.ds_consensus_grouped(_addr(X), P, ld, W, _i32p(perm), _i32p(off), len(off) - 1, _addr(dev_out),
                                      _addr(workspace), workspace_bytes, _stream(stream)), "ds_consensus_grouped")
+
+
+def ds_padded_ld(P: int) -> int:
+    return int(_lib.ds_padded_ld(int(P)))
 
 
 def ds_probe_copy(dst, src, nbytes: int, stream=None) -> None:

@@ -21,6 +21,14 @@ extern "C" const char* ds_status_string(int status) {
     }
 }
 
+extern "C" int64_t ds_padded_ld(int64_t P) {
+    constexpr int64_t kPad = 256;   // elements: 1 KiB of fp32
+    if (P < 0 || P > INT64_MAX - 2 * kPad) return 0;
+    int64_t units = (P + kPad - 1) / kPad;
+    if (units % 2 == 0) ++units;
+    return units * kPad;
+}
+
 namespace {
 
 constexpr uint64_t kGolden = 0x9E3779B97F4A7C15ull;

@@ -37,6 +37,22 @@ def test_status_strings():
     assert not ds.status_string(-99).startswith("DS_")
 
 
+def test_padded_ld_is_the_smallest_odd_multiple_of_256_that_holds_the_row():
+    from paper_2007_03298_amd import workloads as wl
+    r = np.random.default_rng(5)
+    cases = [0, 1, 255, 256, 257, 511, 512, 513, 1_048_576, 11_689_512, 25_557_032, 138_357_544]
+    cases += [int(v) for v in r.integers(0, 2**40, size=2000)]
+    for P in cases:
+        ld = ds.ds_padded_ld(P)
+        assert ld >= P and ld % 256 == 0 and (ld // 256) % 2 == 1
+        assert ld - P < 512                      # at most one pad unit beyond the plain round-up
+        smaller = ld - 512                       # the next odd multiple below does not hold the row
+        assert smaller < P
+        assert ld == wl.padded_ld(P)             # the benchmark layout is the library's recommendation
+    assert ds.ds_padded_ld(-1) == 0
+    assert ds.ds_padded_ld(2**63 - 1) == 0
+
+
 def test_partition_golden(partition_golden):
     _, perms = partition_golden
     for seed, t, W, want in perms:
