@@ -17,11 +17,19 @@
 //     the kernel-argument block through scalar loads (which have their own
 //     wait counter, so fetching an index never waits for data loads), and the
 //     row base addresses live in scalar registers;
-//   - members are accumulated 8/kVpl at a time, i.e. 16 loads of 1 KiB are in
-//     flight per wavefront whatever the group size (kVpl is picked from it);
-//     interior tiles run a predicate-free body so that those loads issue back
-//     to back (a load guarded by a lane predicate gets its own basic block
-//     and the compiler then waits for it before issuing the next one);
+//   - members are accumulated 8/kVpl at a time, i.e. a round issues 16 loads
+//     of 1 KiB per wavefront whatever the group size (kVpl is picked from it);
+//     interior tiles run a predicate-free body (a load guarded by a lane
+//     predicate gets its own basic block and is waited on before the next one
+//     is issued).  As compiled, the loads of a round do not all leave at once:
+//     each member's row index is a scalar load that is waited for before its
+//     two vector loads, and the first sums are taken while the last loads are
+//     still being issued, so about ten loads per wavefront are in flight at a
+//     time and the stores trail one another by a scalar lookup each.  That
+//     pacing was checked against explicit schedules (all 16 loads back to
+//     back, sliding windows of 2..8 member pairs, stores spaced by 0..16
+//     sleep units): the best of them (window of 5 pairs, stores 2 units
+//     apart) is within 0.5 % of this code, back-to-back issue is 3-4 % slower;
 //   - the reduction over members is sequential inside a lane (no cross-lane
 //     traffic is needed: a column never leaves its lane), one mean is formed
 //     per column and stored |group| times, so members end bit-identical;
@@ -30,9 +38,20 @@
 //   - the launch asks for kSyncLdsPad bytes of dynamic LDS that the kernel
 //     never touches.  Its only purpose is to hold the number of wavefronts per
 //     CU at five (about one per SIMD): measured on MI355X, few independent
-//     wavefronts with 16 KiB of loads in flight each sustain 6.3-6.4 TB/s on
-//     this 2:1 read/write mix, full occupancy 5.4 TB/s, and two wavefronts
-//     per CU 4.4 TB/s.
+//     wavefronts sustain 6.3-6.6 TB/s on this 2:1 read/write mix, full
+//     occupancy 5.4 TB/s, and two wavefronts per CU 4.4 TB/s;
+//   - rows that start on 1-KiB boundaries (ds_padded_ld) make every 1-KiB
+//     access one aligned KiB of its row: 2-5 % faster than other 256-byte
+//     alignments.
+// Also measured and not adopted, all on the 32 x 25.6 M fp32 stacks: persistent
+// wavefronts that prefetch the next tile while the current one is reduced and
+// stored (5.0-5.5 TB/s: on this target one counter orders loads and stores, so
+// waiting for a tile's loads also waits for the previous tile's stores),
+// XCD-aware tile orders in runs of 2..64 tiles per XCD (2-12 % slower than the
+// plain order, in which the tiles in flight form one contiguous window of every
+// row), and the other cache-policy bits on loads and stores (sc0, sc1 with or
+// without nt: at best equal to the plain non-temporal hint, without it 10-15 %
+// slower).
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
