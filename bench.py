@@ -91,6 +91,10 @@ def main() -> int:
                     help="configuration 5 only: synchronise layer by layer, one launch per segment in reverse "
                          "layer order, round-robin over K streams with one event per layer (the shape of the "
                          "paper's backward-hook / pre-forward-hook overlap) instead of the single ragged launch")
+    ap.add_argument("--graph", type=int, default=0, metavar="K",
+                    help="also capture K steps (the divisions of iterations 0..K-1, a periodic group list as in "
+                         "the paper's Listing 1) as HIP graphs and time their replay; reported as `graph_replay`, "
+                         "never as `value` (pays off where the step is launch-bound, i.e. configuration 1)")
     ap.add_argument("--dense-rows", action="store_true",
                     help="leading dimension = P (rows not 256-byte aligned) instead of P rounded up to 64")
     ap.add_argument("--probe-copy", type=int, default=0, metavar="N",
@@ -220,6 +224,26 @@ def main() -> int:
     grouped_ms = sum(ge[k].elapsed_time(ge[k + 1]) for k in range(10)) / 10
     grouped_gap = float((dev_grouped - dev_out).abs().max() / dev_out.abs().max().clamp_min(1e-300))
 
+    graph_replay = None
+    if args.graph > 0 and not side:
+        graphs = []
+        for k in range(args.graph):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                stream = torch.cuda.current_stream()       # the capturing stream
+                step(k)
+            graphs.append(g)
+        stream = torch.cuda.current_stream()
+        for k in range(args.warmup):
+            graphs[k % args.graph].replay()
+        torch.cuda.synchronize()
+        g0 = time.perf_counter()
+        for k in range(args.steps):
+            graphs[k % args.graph].replay()
+        torch.cuda.synchronize()
+        g_ms = (time.perf_counter() - g0) / args.steps * 1e3
+        graph_replay = {"graphs": args.graph, "ms_per_step": round(g_ms, 4)}
+
     ms_step = (t1 - t0) / args.steps * 1e3
     sync_ms = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps
     cons_ms = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
@@ -262,6 +286,10 @@ def main() -> int:
     }
     if probe is not None:
         out["probe_copy"] = probe
+    if graph_replay is not None:
+        graph_replay["GBps"] = round((sync_bytes + cons_bytes) / (graph_replay["ms_per_step"] * 1e-3) / 1e9, 1)
+        graph_replay["note"] = "the same step replayed from HIP graphs, one per division of a periodic list; not in value"
+        out["graph_replay"] = graph_replay
     if opt is not None:
         out["config"]["local_opt"] = args.local_opt
         out["roofline"]["kernel"] += " + " + args.local_opt
