@@ -27,13 +27,14 @@ int pack_partition(int32_t W, const int32_t* perm, const int32_t* off, int32_t n
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// Group-sync launch shape.  A workgroup is ONE wavefront; a lane owns vpl
-// vectors of 4 consecutive columns (vpl = 1, 2, 4 or 8, chosen from the group
-// size so that a wavefront keeps kSyncLoadsPerLane 128-bit loads in flight), so
-// a workgroup covers 256*vpl columns of every member row.
+// Group-sync launch shape.  A workgroup is ONE wavefront; a lane owns one
+// vector of 4 consecutive columns, so a workgroup covers 256 columns of every
+// member row (1 KiB per row and load instruction) and loads up to
+// kSyncLoadsPerLane/2 members (x and g each) per round.
 constexpr int kSyncThreads = 64;
+constexpr int kSyncTileCols = kSyncThreads * 4;
 constexpr int kSyncLoadsPerLane = 16;
-// Unit of the ragged plan: 2048 columns = 8 / 4 / 2 / 1 workgroups of vpl 1 / 2 / 4 / 8.
+// Unit of the ragged plan: 2048 columns = 8 workgroups.
 constexpr int kPlanTileCols = 2048;
 
 // One entry of the ragged plan: a run of at most kPlanTileCols columns that

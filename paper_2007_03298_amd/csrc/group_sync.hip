@@ -6,40 +6,43 @@
 // The step is a streaming reduction over the worker axis: 8 (or 6) bytes are
 // read and 4 written per (worker, column) and about one FMA is spent on them,
 // so the kernel is bound by HBM bandwidth and uses no matrix cores.  Mapping:
-//   - a workgroup is ONE wavefront and owns a tile of 256*kVpl consecutive
-//     columns of ONE group; blockIdx.y is the group, blockIdx.x the tile, so
-//     consecutive workgroups walk each member row sequentially;
-//   - a lane owns kVpl vectors of 4 consecutive columns, 64 lanes apart, so
-//     every load/store instruction covers 1 KiB of one row (128-bit per lane,
-//     fully coalesced) and the wavefront owns kVpl consecutive KiB of every
-//     member row;
+//   - a workgroup is ONE wavefront and owns a tile of 256 consecutive columns
+//     of ONE group; blockIdx.y is the group, blockIdx.x the tile, so
+//     consecutive workgroups walk each member row sequentially and the tiles
+//     in flight form one contiguous window of every row;
+//   - a lane owns one vector of 4 consecutive columns, so every load/store
+//     instruction covers 1 KiB of one row (128-bit per lane, fully coalesced).
+//     Wider tiles (2, 4 or 8 vectors per lane) measured 2-20 % slower at every
+//     group size once the occupancy cap follows the bytes in flight;
 //   - member rows are uniform across the wavefront: their indices come from
 //     the kernel-argument block through scalar loads (which have their own
 //     wait counter, so fetching an index never waits for data loads), and the
 //     row base addresses live in scalar registers;
-//   - members are accumulated 8/kVpl at a time, i.e. a round issues 16 loads
-//     of 1 KiB per wavefront whatever the group size (kVpl is picked from it);
-//     interior tiles run a predicate-free body (a load guarded by a lane
-//     predicate gets its own basic block and is waited on before the next one
-//     is issued).  As compiled, the loads of a round do not all leave at once:
-//     each member's row index is a scalar load that is waited for before its
-//     two vector loads, and the first sums are taken while the last loads are
-//     still being issued, so about ten loads per wavefront are in flight at a
-//     time and the stores trail one another by a scalar lookup each.  That
-//     pacing was checked against explicit schedules (all 16 loads back to
-//     back, sliding windows of 2..8 member pairs, stores spaced by 0..16
-//     sleep units): the best of them (window of 5 pairs, stores 2 units
-//     apart) is within 0.5 % of this code, back-to-back issue is 3-4 % slower;
+//   - members are accumulated 8 at a time, i.e. a round issues up to 16 loads
+//     of 1 KiB per wavefront; interior tiles run a predicate-free body (a load
+//     guarded by a lane predicate gets its own basic block and is waited on
+//     before the next one is issued).  As compiled, the loads of a round do
+//     not all leave at once: each member's row index is a scalar load that is
+//     waited for before its two vector loads, and the first sums are taken
+//     while the last loads are still being issued, so about ten loads per
+//     wavefront are in flight at a time and the stores trail one another by a
+//     scalar lookup each.  That pacing was checked against explicit schedules
+//     (all 16 loads back to back, sliding windows of 2..8 member pairs,
+//     stores spaced by 0..16 sleep units): the best of them (window of 5
+//     pairs, stores 2 units apart) is within 0.5 % of this code, back-to-back
+//     issue is 3-4 % slower;
 //   - the reduction over members is sequential inside a lane (no cross-lane
 //     traffic is needed: a column never leaves its lane), one mean is formed
 //     per column and stored |group| times, so members end bit-identical;
 //   - loads and stores carry the non-temporal hint: every byte is touched
 //     exactly once per step;
-//   - the launch asks for kSyncLdsPad bytes of dynamic LDS that the kernel
-//     never touches.  Its only purpose is to hold the number of wavefronts per
-//     CU at five (about one per SIMD): measured on MI355X, few independent
-//     wavefronts sustain 6.3-6.6 TB/s on this 2:1 read/write mix, full
-//     occupancy 5.4 TB/s, and two wavefronts per CU 4.4 TB/s;
+//   - the launch asks for dynamic LDS that the kernel never touches.  Its
+//     only purpose is to cap the number of wavefronts per CU (occupancy_pad
+//     below): measured on MI355X, the memory system sustains most when about
+//     80 KiB of loads are in flight per CU - five wavefronts per CU for groups
+//     of 8 (6.3-6.6 TB/s on this 2:1 read/write mix; full occupancy gives
+//     5.4-5.7, two wavefronts per CU 4.4), ten for groups of 4, twenty for
+//     pairs;
 //   - rows that start on 1-KiB boundaries (ds_padded_ld) make every 1-KiB
 //     access one aligned KiB of its row: 2-5 % faster than other 256-byte
 //     alignments.
@@ -64,6 +67,7 @@ namespace {
 
 using ds::kPlanTileCols;
 using ds::kSyncLoadsPerLane;
+using ds::kSyncTileCols;
 using ds::kSyncThreads;
 using ds::PartitionArg;
 using ds::Tile;
@@ -71,11 +75,19 @@ using ds::Tile;
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-// Dynamic LDS requested per workgroup (never touched): 160 KiB / 32 KiB = 5 wavefronts
-// per CU for the plain step; the extended step moves half as much again per wavefront
-// and does best with 3 per CU (160 / 52).
-constexpr unsigned kSyncLdsPad = 32768;
-constexpr unsigned kSyncLdsPadState = 53248;
+// Occupancy cap.  The launch requests dynamic LDS that the kernel never touches, so
+// that only floor(160 KiB / request) one-wavefront workgroups fit a CU.  The
+// number aimed for keeps about 80 KiB of first-round loads in flight per CU
+// (72 KiB with bf16 gradients): measured on MI355X over group sizes 1..8, fp32
+// and bf16 gradients, with and without the momentum and SWA buffers, the best
+// cap was within 3 % of this rule everywhere (e.g. 16 KiB per wavefront -> 5 per
+// CU, 8 KiB -> 10, 4 KiB -> 20, 24 KiB -> 3).
+constexpr unsigned kLdsPerCu = 160u * 1024u;
+constexpr unsigned kLdsGranule = 2048;
+constexpr int kInFlightHalfKiB = 160;        // fp32 gradients
+constexpr int kInFlightHalfKiBBf16 = 144;    // bf16 gradients
+constexpr int kMinWavesPerCu = 3;
+constexpr int kUncappedWavesPerCu = 26;      // from here on the register file is the limit anyway
 constexpr int64_t kUncappedWorkgroups = 256 * 32;   // one full-occupancy load of the 256 CUs
 
 template <typename V>
@@ -122,44 +134,36 @@ struct Extras {
 // Adds the locally updated parameters of kCount members (perm positions
 // q .. q+kCount-1) to the lane's column sums.  Plain step: y = x - lr*g.
 // With kOpt: d = g + weight_decay*x; kHasV: v' = momentum*v + d is stored back
-// and y = x - lr*v', else y = x - lr*d.  All vector loads are issued back to
-// back before the first use; with kFull nothing is predicated, so the loads
-// sit in one basic block.
-template <typename GT, int kVpl, int kCount, bool kFull, bool kOpt, bool kHasV>
-__device__ __forceinline__ void add_members(f32x4 (&sum)[kVpl], const float* xt, const GT* gt, int64_t ldx,
-                                            int64_t ldg, const Extras& ex, const PartitionArg& part, int q,
-                                            const int (&col)[kVpl], const bool (&live)[kVpl], float lr) {
-    f32x4 x[kCount][kVpl], g[kCount][kVpl], mv[kHasV ? kCount : 1][kVpl];
+// and y = x - lr*v', else y = x - lr*d.  The loads of all kCount members come
+// first in program order; with kFull nothing is predicated, so they sit in one
+// basic block.
+template <typename GT, int kCount, bool kFull, bool kOpt, bool kHasV>
+__device__ __forceinline__ void add_members(f32x4& sum, const float* xt, const GT* gt, int64_t ldx, int64_t ldg,
+                                            const Extras& ex, const PartitionArg& part, int q, int col, bool live,
+                                            float lr) {
+    f32x4 x[kCount], g[kCount], mv[kHasV ? kCount : 1];
 #pragma unroll
     for (int j = 0; j < kCount; ++j) {
         const int64_t row = packed_byte(part.perm, q + j);
-        const float* xr = xt + row * ldx;
-        const GT* gr = gt + row * ldg;
-#pragma unroll
-        for (int v = 0; v < kVpl; ++v) {
-            if (kFull || live[v]) {
-                x[j][v] = stream_load(reinterpret_cast<const f32x4*>(xr + col[v]));
-                g[j][v] = load_grad4(gr + col[v]);
-                if (kHasV) mv[j][v] = stream_load(reinterpret_cast<const f32x4*>(ex.v + row * ex.ldv + col[v]));
-            }
+        if (kFull || live) {
+            x[j] = stream_load(reinterpret_cast<const f32x4*>(xt + row * ldx + col));
+            g[j] = load_grad4(gt + row * ldg + col);
+            if (kHasV) mv[j] = stream_load(reinterpret_cast<const f32x4*>(ex.v + row * ex.ldv + col));
         }
     }
 #pragma unroll
     for (int j = 0; j < kCount; ++j) {
         const int64_t row = kHasV ? packed_byte(part.perm, q + j) : 0;
-#pragma unroll
-        for (int v = 0; v < kVpl; ++v) {
-            if (kFull || live[v]) {
-                if (!kOpt) {
-                    sum[v] += x[j][v] - lr * g[j][v];
-                } else {
-                    f32x4 d = g[j][v] + ex.weight_decay * x[j][v];
-                    if (kHasV) {
-                        d = ex.momentum * mv[j][v] + d;
-                        stream_store(d, reinterpret_cast<f32x4*>(ex.v + row * ex.ldv + col[v]));
-                    }
-                    sum[v] += x[j][v] - lr * d;
+        if (kFull || live) {
+            if (!kOpt) {
+                sum += x[j] - lr * g[j];
+            } else {
+                f32x4 d = g[j] + ex.weight_decay * x[j];
+                if (kHasV) {
+                    d = ex.momentum * mv[j] + d;
+                    stream_store(d, reinterpret_cast<f32x4*>(ex.v + row * ex.ldv + col));
                 }
+                sum += x[j] - lr * d;
             }
         }
     }
@@ -167,77 +171,60 @@ __device__ __forceinline__ void add_members(f32x4 (&sum)[kVpl], const float* xt,
 
 // Writes the mean to kCount members; with kHasS also moves their SWA models:
 // s' = factor*s + (1-factor)*mean (the S loads are issued together first).
-template <int kVpl, int kCount, bool kFull, bool kHasS>
-__device__ __forceinline__ void store_members(const f32x4 (&mean)[kVpl], float* xt, int64_t ldx, const Extras& ex,
-                                              const PartitionArg& part, int q, const int (&col)[kVpl],
-                                              const bool (&live)[kVpl]) {
-    f32x4 s[kHasS ? kCount : 1][kVpl];
+template <int kCount, bool kFull, bool kHasS>
+__device__ __forceinline__ void store_members(const f32x4& mean, float* xt, int64_t ldx, const Extras& ex,
+                                              const PartitionArg& part, int q, int col, bool live) {
+    f32x4 s[kHasS ? kCount : 1];
     if (kHasS) {
 #pragma unroll
         for (int j = 0; j < kCount; ++j) {
             const int64_t row = packed_byte(part.perm, q + j);
-#pragma unroll
-            for (int v = 0; v < kVpl; ++v)
-                if (kFull || live[v]) s[j][v] = stream_load(reinterpret_cast<const f32x4*>(ex.s + row * ex.lds + col[v]));
+            if (kFull || live) s[j] = stream_load(reinterpret_cast<const f32x4*>(ex.s + row * ex.lds + col));
         }
     }
 #pragma unroll
     for (int j = 0; j < kCount; ++j) {
         const int64_t row = packed_byte(part.perm, q + j);
-#pragma unroll
-        for (int v = 0; v < kVpl; ++v) {
-            if (kFull || live[v]) {
-                stream_store(mean[v], reinterpret_cast<f32x4*>(xt + row * ldx + col[v]));
-                if (kHasS) {
-                    const f32x4 moved = ex.factor * s[j][v] + (1.0f - ex.factor) * mean[v];
-                    stream_store(moved, reinterpret_cast<f32x4*>(ex.s + row * ex.lds + col[v]));
-                }
+        if (kFull || live) {
+            stream_store(mean, reinterpret_cast<f32x4*>(xt + row * ldx + col));
+            if (kHasS) {
+                const f32x4 moved = ex.factor * s[j] + (1.0f - ex.factor) * mean;
+                stream_store(moved, reinterpret_cast<f32x4*>(ex.s + row * ex.lds + col));
             }
         }
     }
 }
 
-// One tile of one group.  kFull: the tile has all 256*kVpl columns.
-template <typename GT, int kVpl, bool kFull, bool kOpt, bool kHasV, bool kHasS>
+// One tile of one group.  kFull: the tile has all kSyncTileCols columns.
+template <typename GT, bool kFull, bool kOpt, bool kHasV, bool kHasS>
 __device__ __forceinline__ void sync_tile(float* xt, const GT* gt, int len, int64_t ldx, int64_t ldg,
                                           const Extras& ex, const PartitionArg& part, int first, int n, float lr) {
-    constexpr int kChunk = kSyncLoadsPerLane / 2 / kVpl;   // members per round of loads
-    int col[kVpl];
-    bool live[kVpl];
-    f32x4 sum[kVpl];
+    constexpr int kChunk = kSyncLoadsPerLane / 2;   // members per round of loads
     const int lane = static_cast<int>(threadIdx.x);
-#pragma unroll
-    for (int v = 0; v < kVpl; ++v) {
-        col[v] = (v * 64 + lane) * 4;
-        live[v] = kFull || col[v] + 4 <= len;
-        sum[v] = f32x4{0.f, 0.f, 0.f, 0.f};
-    }
+    const int col = lane * 4;
+    const bool live = kFull || col + 4 <= len;
+    f32x4 sum = {0.f, 0.f, 0.f, 0.f};
     int q = first;
     const int end = first + n;
     for (; q + kChunk <= end; q += kChunk)
-        add_members<GT, kVpl, kChunk, kFull, kOpt, kHasV>(sum, xt, gt, ldx, ldg, ex, part, q, col, live, lr);
+        add_members<GT, kChunk, kFull, kOpt, kHasV>(sum, xt, gt, ldx, ldg, ex, part, q, col, live, lr);
     // remaining members (fewer than kChunk): one specialised, branch-free body each
     switch (end - q) {
 #define DS_REST(k) \
-    case k:        \
-        if (k < kChunk) \
-            add_members<GT, kVpl, (k < kChunk ? k : 1), kFull, kOpt, kHasV>(sum, xt, gt, ldx, ldg, ex, part, q, col, \
-                                                                            live, lr);                              \
-        break;
+    case k: add_members<GT, k, kFull, kOpt, kHasV>(sum, xt, gt, ldx, ldg, ex, part, q, col, live, lr); break;
         DS_REST(1) DS_REST(2) DS_REST(3) DS_REST(4) DS_REST(5) DS_REST(6) DS_REST(7)
 #undef DS_REST
         default: break;
     }
+    static_assert(kChunk == 8, "the remainder switch lists 1..7 members");
     const float nf = static_cast<float>(n);
-#pragma unroll
-    for (int v = 0; v < kVpl; ++v) sum[v] = sum[v] / nf;
+    sum = sum / nf;
     if (!kHasS) {
-        for (int m = first; m < end; ++m) store_members<kVpl, 1, kFull, false>(sum, xt, ldx, ex, part, m, col, live);
+        for (int m = first; m < end; ++m) store_members<1, kFull, false>(sum, xt, ldx, ex, part, m, col, live);
     } else {
         int m = first;
-        for (; m + kChunk <= end; m += kChunk)
-            store_members<kVpl, kChunk, kFull, true>(sum, xt, ldx, ex, part, m, col, live);
-        for (; m < end; ++m) store_members<kVpl, 1, kFull, true>(sum, xt, ldx, ex, part, m, col, live);
+        for (; m + kChunk <= end; m += kChunk) store_members<kChunk, kFull, true>(sum, xt, ldx, ex, part, m, col, live);
+        for (; m < end; ++m) store_members<1, kFull, true>(sum, xt, ldx, ex, part, m, col, live);
     }
     if (!kFull) {
         // ragged end of the tile: fewer than 4 columns, one lane each
@@ -267,13 +254,12 @@ __device__ __forceinline__ void sync_tile(float* xt, const GT* gt, int len, int6
     }
 }
 
-template <typename GT, bool kRagged, int kVpl, bool kOpt, bool kHasV, bool kHasS>
+template <typename GT, bool kRagged, bool kOpt, bool kHasV, bool kHasS>
 __global__ void __launch_bounds__(kSyncThreads)
 group_sync_kernel(float* __restrict__ X, const GT* __restrict__ G, int64_t ldx, int64_t ldg,
                   int64_t P, const Tile* __restrict__ tiles, PartitionArg part, float lr, Extras ex) {
-    static_assert(kVpl == 1 || kVpl == 2 || kVpl == 4 || kVpl == 8, "a lane owns 1, 2, 4 or 8 vectors");
     static_assert(kOpt || (!kHasV && !kHasS), "extra state implies the extended step");
-    constexpr int kTileCols = kSyncThreads * 4 * kVpl;
+    constexpr int kTileCols = kSyncTileCols;
     const uint32_t tile_id = blockIdx.x, group_id = blockIdx.y;
     int64_t start;
     int32_t len;
@@ -301,9 +287,9 @@ group_sync_kernel(float* __restrict__ X, const GT* __restrict__ G, int64_t ldx, 
     const int first = packed_byte(part.off, static_cast<int>(group_id));
     const int n = packed_byte(part.off, static_cast<int>(group_id) + 1) - first;
     if (len == kTileCols)
-        sync_tile<GT, kVpl, true, kOpt, kHasV, kHasS>(X + start, G + start, len, ldx, ldg, ex, part, first, n, lr);
+        sync_tile<GT, true, kOpt, kHasV, kHasS>(X + start, G + start, len, ldx, ldg, ex, part, first, n, lr);
     else
-        sync_tile<GT, kVpl, false, kOpt, kHasV, kHasS>(X + start, G + start, len, ldx, ldg, ex, part, first, n, lr);
+        sync_tile<GT, false, kOpt, kHasV, kHasS>(X + start, G + start, len, ldx, ldg, ex, part, first, n, lr);
 }
 
 struct SegmentScan {
@@ -347,52 +333,49 @@ int check_stacks(const void* X, const void* G, int32_t g_dtype, int64_t ldx, int
     return DS_OK;
 }
 
-// Vectors per lane for a division whose largest group has `largest` members:
-// 2 * members-per-round * vpl = kSyncLoadsPerLane loads in flight per lane.
-int pick_vpl(int32_t largest) { return largest >= 8 ? 1 : largest >= 4 ? 2 : largest >= 2 ? 4 : 8; }
-
-template <typename GT, bool kRagged, int kVpl, bool kOpt, bool kHasV, bool kHasS>
-void launch_one(float* X, const GT* G, int64_t P, int64_t ldx, int64_t ldg, int64_t n_units, const Tile* tiles,
-                const PartitionArg& part, int32_t n_groups, float lr, const Extras& ex, hipStream_t st) {
-    // n_units: flat -> columns; ragged -> plan entries
-    constexpr int kTileCols = kSyncThreads * 4 * kVpl;
-    const int64_t n_tiles = kRagged ? n_units * (kPlanTileCols / kTileCols) : (n_units + kTileCols - 1) / kTileCols;
-    const dim3 grid(static_cast<uint32_t>(n_tiles), static_cast<uint32_t>(n_groups), 1);
-    // the cap on wavefronts per CU pays off for HBM-sized work; a launch that fits the
-    // chip in one go (cache-resident, latency-bound) is better off without it
-    const unsigned lds_pad =
-        n_tiles * n_groups <= kUncappedWorkgroups ? 0u : ((kHasV || kHasS) ? kSyncLdsPadState : kSyncLdsPad);
-    hipLaunchKernelGGL((group_sync_kernel<GT, kRagged, kVpl, kOpt, kHasV, kHasS>), grid, dim3(kSyncThreads, 1, 1),
-                       lds_pad, st, X, G, ldx, ldg, P, tiles, part, lr, ex);
+// Dynamic LDS request (bytes) for a division whose largest group has `largest`
+// members.  A round loads min(largest, 8) members, each 1 KiB of x, 1 KiB (fp32)
+// or 0.5 KiB (bf16) of g and, with momentum, 1 KiB of v per wavefront; the SWA
+// rows are loaded in a later round and do not count.
+unsigned occupancy_pad(int32_t largest, bool bf16, bool has_v, int64_t n_workgroups) {
+    // a launch that fits the chip in one go (cache-resident, latency-bound) is better off uncapped
+    if (n_workgroups <= kUncappedWorkgroups) return 0;
+    const int round = largest < kSyncLoadsPerLane / 2 ? largest : kSyncLoadsPerLane / 2;
+    const int half_kib = round * (2 + (bf16 ? 1 : 2) + (has_v ? 2 : 0));
+    int waves = (bf16 ? kInFlightHalfKiBBf16 : kInFlightHalfKiB) / half_kib;
+    if (waves < kMinWavesPerCu) waves = kMinWavesPerCu;
+    if (waves >= kUncappedWavesPerCu) return 0;
+    return kLdsPerCu / static_cast<unsigned>(waves) / kLdsGranule * kLdsGranule;
 }
 
 template <typename GT, bool kRagged, bool kOpt, bool kHasV, bool kHasS>
-void launch_vpl(int vpl, float* X, const GT* G, int64_t P, int64_t ldx, int64_t ldg, int64_t n_units,
-                const Tile* tiles, const PartitionArg& part, int32_t n_groups, float lr, const Extras& ex,
+void launch_one(float* X, const GT* G, int64_t P, int64_t ldx, int64_t ldg, int64_t n_units, const Tile* tiles,
+                const PartitionArg& part, int32_t largest, int32_t n_groups, float lr, const Extras& ex,
                 hipStream_t st) {
-    switch (vpl) {
-        case 1: launch_one<GT, kRagged, 1, kOpt, kHasV, kHasS>(X, G, P, ldx, ldg, n_units, tiles, part, n_groups, lr, ex, st); break;
-        case 2: launch_one<GT, kRagged, 2, kOpt, kHasV, kHasS>(X, G, P, ldx, ldg, n_units, tiles, part, n_groups, lr, ex, st); break;
-        case 4: launch_one<GT, kRagged, 4, kOpt, kHasV, kHasS>(X, G, P, ldx, ldg, n_units, tiles, part, n_groups, lr, ex, st); break;
-        default: launch_one<GT, kRagged, 8, kOpt, kHasV, kHasS>(X, G, P, ldx, ldg, n_units, tiles, part, n_groups, lr, ex, st); break;
-    }
+    // n_units: flat -> columns; ragged -> plan entries
+    constexpr int kTileCols = kSyncTileCols;
+    const int64_t n_tiles = kRagged ? n_units * (kPlanTileCols / kTileCols) : (n_units + kTileCols - 1) / kTileCols;
+    const dim3 grid(static_cast<uint32_t>(n_tiles), static_cast<uint32_t>(n_groups), 1);
+    const unsigned lds_pad = occupancy_pad(largest, sizeof(GT) == 2, kHasV, n_tiles * n_groups);
+    hipLaunchKernelGGL((group_sync_kernel<GT, kRagged, kOpt, kHasV, kHasS>), grid, dim3(kSyncThreads, 1, 1),
+                       lds_pad, st, X, G, ldx, ldg, P, tiles, part, lr, ex);
 }
 
 template <typename GT, bool kRagged>
-void launch_state(int vpl, float* X, const GT* G, int64_t P, int64_t ldx, int64_t ldg, int64_t n_units,
+void launch_state(int32_t largest, float* X, const GT* G, int64_t P, int64_t ldx, int64_t ldg, int64_t n_units,
                   const Tile* tiles, const PartitionArg& part, int32_t n_groups, float lr, bool opt, const Extras& ex,
                   hipStream_t st) {
     const bool has_v = ex.v != nullptr, has_s = ex.s != nullptr;
     if (!opt)
-        launch_vpl<GT, kRagged, false, false, false>(vpl, X, G, P, ldx, ldg, n_units, tiles, part, n_groups, lr, ex, st);
+        launch_one<GT, kRagged, false, false, false>(X, G, P, ldx, ldg, n_units, tiles, part, largest, n_groups, lr, ex, st);
     else if (has_v && has_s)
-        launch_vpl<GT, kRagged, true, true, true>(vpl, X, G, P, ldx, ldg, n_units, tiles, part, n_groups, lr, ex, st);
+        launch_one<GT, kRagged, true, true, true>(X, G, P, ldx, ldg, n_units, tiles, part, largest, n_groups, lr, ex, st);
     else if (has_v)
-        launch_vpl<GT, kRagged, true, true, false>(vpl, X, G, P, ldx, ldg, n_units, tiles, part, n_groups, lr, ex, st);
+        launch_one<GT, kRagged, true, true, false>(X, G, P, ldx, ldg, n_units, tiles, part, largest, n_groups, lr, ex, st);
     else if (has_s)
-        launch_vpl<GT, kRagged, true, false, true>(vpl, X, G, P, ldx, ldg, n_units, tiles, part, n_groups, lr, ex, st);
+        launch_one<GT, kRagged, true, false, true>(X, G, P, ldx, ldg, n_units, tiles, part, largest, n_groups, lr, ex, st);
     else
-        launch_vpl<GT, kRagged, true, false, false>(vpl, X, G, P, ldx, ldg, n_units, tiles, part, n_groups, lr, ex, st);
+        launch_one<GT, kRagged, true, false, false>(X, G, P, ldx, ldg, n_units, tiles, part, largest, n_groups, lr, ex, st);
 }
 
 template <bool kRagged>
@@ -400,12 +383,11 @@ int launch(void* X, const void* G, int32_t g_dtype, int64_t P, int64_t ldx, int6
            const Tile* tiles, const PartitionArg& part, int32_t largest, int32_t n_groups, float lr, bool opt,
            const Extras& ex, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const int vpl = pick_vpl(largest);
     if (g_dtype == DS_F32)
-        launch_state<float, kRagged>(vpl, static_cast<float*>(X), static_cast<const float*>(G), P, ldx, ldg, n_units,
+        launch_state<float, kRagged>(largest, static_cast<float*>(X), static_cast<const float*>(G), P, ldx, ldg, n_units,
                                      tiles, part, n_groups, lr, opt, ex, st);
     else
-        launch_state<uint16_t, kRagged>(vpl, static_cast<float*>(X), static_cast<const uint16_t*>(G), P, ldx, ldg,
+        launch_state<uint16_t, kRagged>(largest, static_cast<float*>(X), static_cast<const uint16_t*>(G), P, ldx, ldg,
                                         n_units, tiles, part, n_groups, lr, opt, ex, st);
     return hipGetLastError() == hipSuccess ? DS_OK : DS_ERR_HIP;
 }
@@ -455,7 +437,7 @@ int group_sync_flat(void* X, const void* G, int32_t g_dtype, int64_t P, int64_t 
     int32_t max_size = 0, equal_size = 0;
     rc = ds::pack_partition(W, perm, off, n_groups, &part, &max_size, &equal_size);
     if (rc != DS_OK) return rc;
-    if (P / (kSyncThreads * 4) >= INT32_MAX) return DS_ERR_BAD_SHAPE;   // grid.x limit at the narrowest tile
+    if (P / kSyncTileCols >= INT32_MAX) return DS_ERR_BAD_SHAPE;   // grid.x limit
     if (P == 0) return DS_OK;
     return launch<false>(X, G, g_dtype, P, ldx, ldg, P, nullptr, part, max_size, n_groups, lr, extended, ex, stream);
 }
