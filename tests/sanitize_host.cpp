@@ -20,6 +20,20 @@ static int below(int n) { return static_cast<int>(next_u64() % static_cast<uint6
 
 int main() {
     long checked = 0;
+    // recommended row pitch: extremes first (signed overflow would trip the sanitizer), then random lengths
+    const int64_t edge[] = {INT64_MIN, -1, 0, 1, 255, 256, 257, INT64_MAX - 1024, INT64_MAX - 512, INT64_MAX - 511, INT64_MAX};
+    for (const int64_t P : edge) {
+        const int64_t ld = ds_padded_ld(P);
+        if (ld != 0 && (ld < P || ld % 256 != 0 || (ld / 256) % 2 != 1)) { std::printf("ds_padded_ld(%lld) = %lld\n", (long long)P, (long long)ld); return 1; }
+    }
+    for (int iter = 0; iter < 20000; ++iter) {
+        const int64_t P = static_cast<int64_t>(next_u64() >> (1 + below(62)));
+        const int64_t ld = ds_padded_ld(P);
+        if (ld == 0 ? P <= INT64_MAX - 1024 : (ld < P || ld - P >= 512 || ld % 256 != 0 || (ld / 256) % 2 != 1)) {
+            std::printf("ds_padded_ld(%lld) = %lld\n", (long long)P, (long long)ld);
+            return 1;
+        }
+    }
     for (int iter = 0; iter < 20000; ++iter) {
         const int W = 1 + below(DS_MAX_W);
         std::vector<int32_t> sizes;
