@@ -159,7 +159,8 @@ int ds_pattern_period(int32_t W, const int32_t* rack_of, const uint8_t* slow_rac
  *   perm,off host; any valid division of the workers (as ds_partition writes it,
  *            or any other: the call does not care how the groups were chosen)
  *   lr       learning rate
- * Alignment: X and G 16-byte aligned.
+ * Alignment: X and G 16-byte aligned.  Fastest with 1-KiB-aligned bases and
+ * ldx = ldg = ds_padded_ld(P) (every row on a 1-KiB boundary).
  * Errors: DS_ERR_NULL, DS_ERR_BAD_W, DS_ERR_BAD_SIZES, DS_ERR_BAD_PART,
  *         DS_ERR_BAD_SHAPE, DS_ERR_ALIGN, DS_ERR_DTYPE, DS_ERR_HIP.
  */
@@ -175,7 +176,8 @@ int ds_group_sync(void* X, const void* G, int32_t g_dtype, int64_t P, int64_t ld
  * untouched.
  *
  * A segment is columns offset .. offset+length-1 of every row.  Rules: length
- * >= 0 (empty segments are allowed), offset >= 0 and a multiple of 8 elements,
+ * >= 0 (empty segments are allowed), offset >= 0 and a multiple of 8 elements
+ * (fastest: a multiple of 256, so that segments start on 1-KiB boundaries),
  * offset+length <= min(ldx, ldg), segments pairwise disjoint.
  *
  * The segment list is turned once into a device-side tile table ("plan"):
