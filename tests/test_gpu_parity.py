@@ -105,6 +105,36 @@ def test_step_matches_oracle_small(W, sizes, P, ldx, ldg, bf16):
     assert not np.array_equal(got[:, :P], Xh0[:, :P])
 
 
+# Launches of more than one chip-load of workgroups are held to a number of
+# wavefronts per CU that depends on the largest group, the gradient type and
+# the momentum buffer; the small cases above never get there.
+@pytest.mark.parametrize("W,sizes,bf16,use_v", [(8, [1, 2, 5], False, False), (8, [3, 5], True, False),
+                                                (6, [1] * 6, False, False), (6, [2, 2, 2], True, True),
+                                                (12, [1, 11], False, True), (4, [4], False, False)])
+def test_occupancy_capped_launches_match_oracle(W, sizes, bf16, use_v):
+    P = 256 * 8192 // len(sizes) + 256 * 700 + 77          # > 8192 workgroups, ragged end
+    ld = ds.ds_padded_ld(P)
+    X, G = random_stacks(31 + W, W, ld, ld, bf16)
+    V = torch.empty_like(X).normal_(generator=torch.Generator(device=DEV).manual_seed(5)) if use_v else None
+    Xh, Gh = wl.tensor_to_numpy(X), wl.tensor_to_numpy(G)
+    Vh = wl.tensor_to_numpy(V) if use_v else None
+    perm, off = ds.ds_partition(9, 4, W, sizes)
+    if use_v:
+        ds.ds_group_sync_opt(X, G, ds.DS_BF16 if bf16 else ds.DS_F32, P, ld, ld, W, perm, off, 0.02,
+                             ds.local_opt(V, ld, 0.9, 1e-3, None, 0, 0.0))
+        oracle.step_opt(Xh, Gh, perm, off, 0.02, V=Vh, momentum=0.9, weight_decay=1e-3, col0=0, ncols=P)
+    else:
+        ds.ds_group_sync(X, G, ds.DS_BF16 if bf16 else ds.DS_F32, P, ld, ld, W, perm, off, 0.02)
+        oracle.step(Xh, Gh, perm, off, 0.02, 0, P)
+    torch.cuda.synchronize()
+    got = wl.tensor_to_numpy(X)
+    assert scaled_error(got[:, :P], Xh[:, :P]) <= TOL_F32
+    assert np.array_equal(got[:, P:], Xh[:, P:])
+    assert_members_identical(got[:, :P], perm, off)
+    if use_v:
+        assert scaled_error(wl.tensor_to_numpy(V)[:, :P], Vh[:, :P]) <= TOL_F32
+
+
 def test_group_of_all_workers_is_mean_gradient_sgd_on_gpu():
     W, P = 16, 6001
     ld = 6004
