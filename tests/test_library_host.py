@@ -30,6 +30,22 @@ def test_library_exports_every_declared_symbol():
         assert getattr(lib, n) is not None
 
 
+def test_header_is_c99_and_a_plain_c_client_links_and_runs(tmp_path, partition_golden):
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("needs gcc")
+    exe = str(tmp_path / "abi_client")
+    libdir = os.path.dirname(binding.LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(ROOT, "include"),
+                    os.path.join(ROOT, "tests", "abi_client.c"), "-L", libdir, "-l:libdssync.so",
+                    "-Wl,-rpath," + libdir, "-o", exe], check=True)
+    res = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert res.returncode == 0, (res.returncode, res.stdout, res.stderr)
+    want = [p for s, t, W, p in partition_golden[1] if (s, t, W) == (0, 0, 8)][0]
+    assert res.stdout.split("perm")[1].split() == [str(v) for v in want]
+
+
 def test_status_strings():
     for code in range(0, -10, -1):
         s = ds.status_string(code)
