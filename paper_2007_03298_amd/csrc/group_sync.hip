@@ -78,14 +78,16 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 // Occupancy cap.  The launch requests dynamic LDS that the kernel never touches, so
 // that only floor(160 KiB / request) one-wavefront workgroups fit a CU.  The
 // number aimed for keeps about 80 KiB of first-round loads in flight per CU
-// (72 KiB with bf16 gradients): measured on MI355X over group sizes 1..8, fp32
-// and bf16 gradients, with and without the momentum and SWA buffers, the best
-// cap was within 3 % of this rule everywhere (e.g. 16 KiB per wavefront -> 5 per
-// CU, 8 KiB -> 10, 4 KiB -> 20, 24 KiB -> 3).
+// (with bf16 gradients 60 KiB for pairs rising to 72 KiB for groups of 8):
+// measured on MI355X over group sizes 1..8, fp32 and bf16 gradients, with and
+// without the momentum and SWA buffers, the best cap was within 3.5 % of this
+// rule everywhere (e.g. 16 KiB per wavefront -> 5 per CU, 8 KiB -> 10,
+// 4 KiB -> 20, 24 KiB -> 3).
 constexpr unsigned kLdsPerCu = 160u * 1024u;
 constexpr unsigned kLdsGranule = 2048;
 constexpr int kInFlightHalfKiB = 160;        // fp32 gradients
-constexpr int kInFlightHalfKiBBf16 = 144;    // bf16 gradients
+constexpr int kInFlightHalfKiBBf16 = 112;    // bf16 gradients: this plus 4 per member of a round ...
+constexpr int kInFlightHalfKiBBf16V = 144;   // ... or this with the momentum buffer
 constexpr int kMinWavesPerCu = 3;
 constexpr int kUncappedWavesPerCu = 26;      // from here on the register file is the limit anyway
 constexpr int64_t kUncappedWorkgroups = 256 * 32;   // one full-occupancy load of the 256 CUs
@@ -342,7 +344,8 @@ unsigned occupancy_pad(int32_t largest, bool bf16, bool has_v, int64_t n_workgro
     if (n_workgroups <= kUncappedWorkgroups) return 0;
     const int round = largest < kSyncLoadsPerLane / 2 ? largest : kSyncLoadsPerLane / 2;
     const int half_kib = round * (2 + (bf16 ? 1 : 2) + (has_v ? 2 : 0));
-    int waves = (bf16 ? kInFlightHalfKiBBf16 : kInFlightHalfKiB) / half_kib;
+    const int target = !bf16 ? kInFlightHalfKiB : has_v ? kInFlightHalfKiBBf16V : kInFlightHalfKiBBf16 + 4 * round;
+    int waves = target / half_kib;
     if (waves < kMinWavesPerCu) waves = kMinWavesPerCu;
     if (waves >= kUncappedWavesPerCu) return 0;
     return kLdsPerCu / static_cast<unsigned>(waves) / kLdsGranule * kLdsGranule;
