@@ -27,6 +27,30 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published
+PROBE_SRC = os.path.join(ROOT, "bench_probe.hip")
+PROBE_LIB = os.path.join(ROOT, "libbench_probe.so")
+
+
+def build_probe() -> str:
+    """Compile the plain copy kernel that serves as yardstick (bench_probe.hip, gfx950)."""
+    from paper_2007_03298_amd.build import compile_shared
+    return compile_shared([PROBE_SRC], PROBE_LIB)
+
+
+def load_probe():
+    """The copy kernel as ``probe_copy(dst, src, nbytes, stream)``; it must have been built."""
+    import ctypes
+    if not os.path.exists(PROBE_LIB):
+        raise RuntimeError("libbench_probe.so is not built: run `python bench.py --build-probe`")
+    lib = ctypes.CDLL(PROBE_LIB)
+    lib.bench_probe_copy.restype = ctypes.c_int
+    lib.bench_probe_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+
+    def probe_copy(dst, src, nbytes, stream):
+        rc = lib.bench_probe_copy(dst.data_ptr(), src.data_ptr(), nbytes, stream.cuda_stream)
+        if rc != 0:
+            raise RuntimeError("bench_probe_copy failed: %d" % rc)
+    return probe_copy
 
 
 def measured_traffic(name: str, workload: str):
@@ -103,7 +127,11 @@ def main() -> int:
     ap.add_argument("--probe-copy", type=int, default=0, metavar="N",
                     help="also launch the plain copy kernel N times on a stack-sized buffer before the "
                          "timed region (yardstick for bandwidth and for profiler counter scaling)")
+    ap.add_argument("--build-probe", action="store_true", help="compile bench_probe.hip and exit")
     args = ap.parse_args()
+    if args.build_probe:
+        print(build_probe())
+        return 0
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (W simulated workers stacked in one HBM); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
@@ -125,8 +153,8 @@ def main() -> int:
         P = sum(n for _, n in segs)
         plan_bytes = ds.ds_ragged_plan_bytes(segs)
         plan = torch.empty(plan_bytes, dtype=torch.uint8, device=dev)
-        ds.ds_ragged_plan(segs, ld, ld, plan, plan_bytes)
         packed = ds.pack_segments(segs)
+        plan_id = ds.ds_ragged_plan(packed, ld, ld, plan, plan_bytes)
     else:
         P = cfg.P
         ld = P if args.dense_rows else wl.padded_ld(P)   # rows start on 256-byte boundaries
@@ -178,7 +206,7 @@ def main() -> int:
             layerwise(t, perm, off)
         elif cfg.ragged:
             ds.ds_group_sync_ragged_opt(X, Gs[t % n_grad], ds.DS_BF16, packed, ld, ld, W, perm, off, cfg.lr, opt,
-                                        plan, plan_bytes, stream)
+                                        plan, plan_bytes, plan_id, stream)
         else:
             ds.ds_group_sync_opt(X, Gs[t % n_grad], ds.DS_F32, P, ld, ld, W, perm, off, cfg.lr, opt, stream)
         if ev:
@@ -189,13 +217,14 @@ def main() -> int:
 
     probe = None
     if args.probe_copy > 0:
+        probe_copy = load_probe()
         Y = torch.empty_like(X)
         nbytes = X.numel() * 4
         pe = [torch.cuda.Event(enable_timing=True) for _ in range(args.probe_copy + 1)]
-        ds.ds_probe_copy(Y, X, nbytes, stream)
+        probe_copy(Y, X, nbytes, stream)
         pe[0].record(stream)
         for k in range(args.probe_copy):
-            ds.ds_probe_copy(Y, X, nbytes, stream)
+            probe_copy(Y, X, nbytes, stream)
             pe[k + 1].record(stream)
         torch.cuda.synchronize()
         pms = sum(pe[k].elapsed_time(pe[k + 1]) for k in range(args.probe_copy)) / args.probe_copy

@@ -21,9 +21,15 @@
  *     Host arrays are consumed before the call returns.  Device buffers must
  *     stay valid until `stream` has executed the enqueued work.
  *   - GPU work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
- *     the default stream).  No entry point synchronises, allocates or frees
- *     device memory, except ds_ragged_plan (a one-off set-up call, see there).
- *   - The library keeps no state between calls.
+ *     the default stream).  No entry point synchronises, copies between host
+ *     and device, or allocates or frees device memory: a GPU entry point
+ *     issues kernel launches and nothing else, so each of them can be
+ *     recorded into a HIP graph.
+ *   - The library keeps no state between calls, apart from two attributes of
+ *     each device (number of compute units, LDS per compute unit), which are
+ *     read once per process and device on the first launch there.
+ *   - One launch covers at most DS_MAX_COLUMNS columns; longer rows are
+ *     DS_ERR_BAD_SHAPE (columns are independent, so the caller can split them).
  *   - Row-major stacks: element (worker i, column p) of a stack with leading
  *     dimension ld is at base + i*ld + p, ld >= P.  Replica stacks are fp32.
  */
@@ -50,8 +56,9 @@ typedef enum {
     DS_ERR_DTYPE     = -7,  /* g_dtype is neither DS_F32 nor DS_BF16                       */
     DS_ERR_WORKSPACE = -8,  /* workspace / plan buffer NULL, misaligned or too small       */
     DS_ERR_HIP       = -9,  /* a HIP call or kernel launch failed                          */
-    DS_ERR_TOPOLOGY  = -10  /* rack table: index outside 0..n_racks-1, an unused rack index,
+    DS_ERR_TOPOLOGY  = -10, /* rack table: index outside 0..n_racks-1, an unused rack index,
                                or a rack whose workers all have NIC contention             */
+    DS_ERR_HOST_MEMORY = -11 /* a host-side allocation inside the call failed              */
 } ds_status;
 
 /* gradient element type */
@@ -61,14 +68,19 @@ enum { DS_F32 = 0, DS_BF16 = 1 };
    kernel-argument block, so no host-to-device copy sits on the path. */
 #define DS_MAX_W 64
 
+/* Largest number of columns one launch covers: the grid of one-wavefront
+   workgroups of 256 columns must stay below HIP's limit of 2^32 threads along
+   x (about 17.18e9 columns, 68.7 GB per fp32 row). */
+#define DS_MAX_COLUMNS ((((int64_t)1 << 26) - 1) * 256)
+
 /* Human-readable name of a status code (static storage, never NULL). */
 const char* ds_status_string(int status);
 
 /*
  * ds_partition -- the group of every worker in iteration t.
  *
- * Paper: Listing 1 ("pick the proper group to synchronize for worker i in the
- * iteration t") and Sec. IV-B2 (each iteration's groups are disjoint and cover
+ * Paper: Listing 1 (the per-iteration lookup of worker i's group in the group
+ * list) and Sec. IV-B2 (each iteration's groups are disjoint and cover
  * all workers; groups may differ in size, Sec. III-A).  The paper's list is
  * derived from the network topology; this routine draws iteration t's entry
  * with a counter-based shuffle instead, so any (seed, t) can be evaluated in
@@ -140,6 +152,45 @@ int ds_pattern_period(int32_t W, const int32_t* rack_of, const uint8_t* slow_rac
                       const uint8_t* slow_worker, uint64_t* period_out);
 
 /*
+ * ds_pattern_check -- does a periodic list of divisions meet the premise of
+ * the paper's consensus bound, and how fast does it contract?
+ *
+ * Paper: Sec. IV-B2.  Division k of the period has the mixing matrix W_k
+ * (w_ij = 1/|group| for two members of one group, else 0) and one period is
+ * M = W_{B-1} ... W_0.  Lemma 1 requires the period to be connected (the
+ * union, over the period, of the groups taken as complete graphs is a single
+ * component) and bounds the consensus error after k periods by rho^k with rho
+ * the second largest eigenvalue modulus of M.  This routine reports
+ *   connected_out  1 if the union graph is one component, else 0 (union-find
+ *                  over the groups of the period);
+ *   rho_out        the spectral radius of M - 11^T/W, i.e. that second
+ *                  eigenvalue modulus (M is a product of symmetric matrices
+ *                  but not symmetric itself, so its eigenvalues may be
+ *                  complex; the radius is taken as lim ||A^(2^j)||^(1/2^j) by
+ *                  repeated squaring in fp64, accurate to about 1e-12);
+ *   sigma_out      || M - 11^T/W ||_2 >= rho, the factor by which one period
+ *                  is guaranteed to shrink || X - mean ||_F for every X (the
+ *                  square root of the spectral radius of A^T A, same method).
+ * rho < 1, sigma < 1 and connected are equivalent (every W_k is an orthogonal
+ * projector, so ||M x|| = ||x|| only for x constant on every component).
+ * The list may come from ds_pattern, ds_partition or anywhere else.
+ *
+ *   W          workers, 1..DS_MAX_W
+ *   B          divisions in the period, >= 1
+ *   perms      host [B*W]:     perm of division k at perms + k*W
+ *   offs       host [B*(W+1)]: off of division k at offs + k*(W+1), the first
+ *              n_groups[k]+1 entries used
+ *   n_groups   host [B]
+ *   rho_out, sigma_out  may each be NULL (that part is then skipped)
+ * Host only, fp64, O(B*W^2 + W^3) work, no allocation.
+ * Errors: DS_ERR_NULL, DS_ERR_BAD_W, DS_ERR_BAD_SHAPE (B < 1), DS_ERR_BAD_SIZES,
+ *         DS_ERR_BAD_PART (a list entry is not a division of the workers).
+ */
+int ds_pattern_check(int32_t W, int32_t B, const int32_t* perms, const int32_t* offs,
+                     const int32_t* n_groups, int32_t* connected_out, double* rho_out,
+                     double* sigma_out);
+
+/*
  * ds_group_sync -- local SGD update fused with the in-group parameter average.
  *
  * Paper: Listing 1, optimizer.step() followed by Average(model, group);
@@ -182,15 +233,32 @@ int ds_group_sync(void* X, const void* G, int32_t g_dtype, int64_t P, int64_t ld
  *
  * The segment list is turned once into a device-side tile table ("plan"):
  *   ds_ragged_plan_bytes   bytes the plan needs (0 if every segment is empty)
- *   ds_ragged_plan         builds the table on the host, copies it to `plan`
- *                          on `stream` and WAITS for the copy (set-up call,
- *                          once per layer list)
- *   ds_group_sync_ragged   kernel launch only; `segs`/`S` must be the list the
- *                          plan was built from (only its tile count is re-derived)
- * plan: dev, 16-byte aligned, at least ds_ragged_plan_bytes bytes.
+ *   ds_ragged_plan         set-up call, once per layer list: checks the list
+ *                          and enqueues small kernels on `stream` that write
+ *                          the table (the segments travel in the kernel
+ *                          arguments, 96 per launch: no copy, no wait).
+ *                          *plan_id_out receives the identity of the plan, a
+ *                          hash of the segment list that is never 0 (0 if the
+ *                          list has no columns); it is also stored in the
+ *                          plan's first entry.
+ *   ds_group_sync_ragged   kernel launch only.  `segs`/`S` must be the list
+ *                          the plan was built from and `plan_id` the value
+ *                          ds_ragged_plan returned for this buffer: a plan_id
+ *                          that is not that of `segs` is DS_ERR_WORKSPACE,
+ *                          reported on the host before anything is enqueued.
+ *                          On the device every workgroup compares plan_id and
+ *                          the entry count with the plan's first entry and
+ *                          leaves the stacks untouched if they differ (a
+ *                          buffer that holds another plan, or none), and an
+ *                          entry that points outside the rows is skipped.
+ * plan: dev, 16-byte aligned, at least ds_ragged_plan_bytes bytes; it must not
+ * be written by anyone else while launches that use it are pending.
  * Other arguments, alignment and errors as ds_group_sync; a bad segment table
- * is DS_ERR_BAD_SHAPE (or DS_ERR_ALIGN for an offset), a bad plan buffer
- * DS_ERR_WORKSPACE.
+ * is DS_ERR_BAD_SHAPE (or DS_ERR_ALIGN for an offset), a bad plan buffer or
+ * plan_id DS_ERR_WORKSPACE, a list whose lengths, each rounded up to a
+ * multiple of 2048 columns, add up to more than DS_MAX_COLUMNS
+ * DS_ERR_BAD_SHAPE; ds_ragged_plan may also return DS_ERR_HOST_MEMORY (its
+ * overlap check sorts a host copy of the list).
  */
 typedef struct {
     int64_t offset;  /* first column, in elements */
@@ -200,12 +268,12 @@ typedef struct {
 size_t ds_ragged_plan_bytes(const ds_segment* segs, int32_t S);
 
 int ds_ragged_plan(const ds_segment* segs, int32_t S, int64_t ldx, int64_t ldg, void* plan,
-                   size_t plan_bytes, void* stream);
+                   size_t plan_bytes, uint64_t* plan_id_out, void* stream);
 
 int ds_group_sync_ragged(void* X, const void* G, int32_t g_dtype, const ds_segment* segs, int32_t S,
                          int64_t ldx, int64_t ldg, int32_t W, const int32_t* perm,
                          const int32_t* off, int32_t n_groups, float lr, const void* plan,
-                         size_t plan_bytes, void* stream);
+                         size_t plan_bytes, uint64_t plan_id, void* stream);
 
 /*
  * ds_group_sync_opt / ds_group_sync_ragged_opt -- the same step with the fuller
@@ -248,16 +316,22 @@ int ds_group_sync_opt(void* X, const void* G, int32_t g_dtype, int64_t P, int64_
 int ds_group_sync_ragged_opt(void* X, const void* G, int32_t g_dtype, const ds_segment* segs, int32_t S,
                              int64_t ldx, int64_t ldg, int32_t W, const int32_t* perm,
                              const int32_t* off, int32_t n_groups, float lr, const ds_local_opt* opt,
-                             const void* plan, size_t plan_bytes, void* stream);
+                             const void* plan, size_t plan_bytes, uint64_t plan_id, void* stream);
 
 /*
  * ds_consensus -- how far every replica is from the mean replica.
  *
  * Paper: Sec. IV-B2; the left-hand side of Lemma 1 for worker i, un-squared:
  *     xbar[p] = (1/W) * sum_i X[i,p];   dev_out[i] = sqrt( sum_{p<P} (X[i,p] - xbar[p])^2 )
- * The column mean and the differences are formed in fp64, so identical
- * replicas give exactly 0.  The result is deterministic (fixed reduction
- * tree, no floating-point atomics).  X is read once.
+ * Arithmetic: the column mean is formed in fp64 and split into an fp32 pair
+ * hi + lo; the difference (x - hi) - lo and its square are fp32, so the
+ * rounding error is relative to the difference itself and identical replicas
+ * give exactly 0.  A lane sums the squares of at most 128 columns per worker
+ * in fp32 before the sum is widened; everything above that (across lanes,
+ * wavefronts, workgroups) is fp64.  Relative error of a norm: below 4e-6 in the
+ * worst case and about 3e-7 typically, whatever P.  The result is
+ * deterministic (fixed reduction tree, no floating-point atomics).  X is read
+ * once.
  *
  *   X          dev fp32 [W, ld], read only; 16-byte aligned, ld >= P, ld % 4 == 0
  *   dev_out    dev fp64 [W], written
@@ -303,17 +377,6 @@ int ds_consensus_grouped(const void* X, int64_t P, int64_t ld, int32_t W, const 
  * Host only.  Returns 0 if P < 0 or the result would not fit in int64_t.
  */
 int64_t ds_padded_ld(int64_t P);
-
-/*
- * ds_probe_copy -- measurement aid, not a step of the method: a plain
- * device-to-device streaming copy of `bytes` bytes (reads `bytes`, writes
- * `bytes`).  The benchmark uses it as the attainable-bandwidth yardstick and
- * to scale the profiler's HBM byte counters against a launch whose traffic is
- * known exactly.
- *   dst, src   dev, 16-byte aligned, non-overlapping; bytes a multiple of 16
- * Errors: DS_ERR_NULL, DS_ERR_ALIGN, DS_ERR_BAD_SHAPE, DS_ERR_HIP.
- */
-int ds_probe_copy(void* dst, const void* src, size_t bytes, void* stream);
 
 #ifdef __cplusplus
 }

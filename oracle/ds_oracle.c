@@ -9,8 +9,8 @@
  *
  * What is implemented, and where the paper defines it:
  *   orc_partition  -- the per-iteration division of the N workers into
- *                     non-overlapping groups (Listing 1, "pick the proper group
- *                     ... in the iteration t"; Sec. IV-B2, W_k = disjoint fully
+ *                     non-overlapping groups (Listing 1, the lookup of worker
+ *                     i's group for iteration t; Sec. IV-B2, W_k = disjoint fully
  *                     connected sub-graphs covering all nodes).  The paper's own
  *                     list is topology derived; here the list entry for
  *                     iteration t is drawn by a counter-based shuffle whose

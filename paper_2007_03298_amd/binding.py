@@ -20,8 +20,12 @@ LIB_PATH = os.path.join(_HERE, "libdssync.so")
 DS_F32, DS_BF16 = 0, 1
 DS_MAX_W = 64
 
-EXPORTS = ("ds_status_string", "ds_partition", "ds_pattern", "ds_pattern_period", "ds_group_sync", "ds_ragged_plan_bytes", "ds_ragged_plan",
-           "ds_group_sync_ragged", "ds_group_sync_opt", "ds_group_sync_ragged_opt", "ds_consensus_workspace_bytes", "ds_consensus", "ds_consensus_grouped", "ds_probe_copy", "ds_padded_ld")
+DS_MAX_COLUMNS = ((1 << 26) - 1) * 256
+
+EXPORTS = ("ds_status_string", "ds_partition", "ds_pattern", "ds_pattern_period", "ds_pattern_check", "ds_group_sync",
+           "ds_ragged_plan_bytes", "ds_ragged_plan", "ds_group_sync_ragged", "ds_group_sync_opt",
+           "ds_group_sync_ragged_opt", "ds_consensus_workspace_bytes", "ds_consensus", "ds_consensus_grouped",
+           "ds_padded_ld")
 
 
 class DsError(RuntimeError):
@@ -57,21 +61,24 @@ def _load() -> ctypes.CDLL:
     lib.ds_pattern.argtypes = [i32, i32p, u8p, i32, u8p, u64, i32p, i32p, i32p]
     lib.ds_pattern_period.restype = ctypes.c_int
     lib.ds_pattern_period.argtypes = [i32, i32p, u8p, i32, u8p, ctypes.POINTER(u64)]
+    f64p = ctypes.POINTER(ctypes.c_double)
+    lib.ds_pattern_check.restype = ctypes.c_int
+    lib.ds_pattern_check.argtypes = [i32, i32, i32p, i32p, i32p, i32p, f64p, f64p]
     lib.ds_group_sync.restype = ctypes.c_int
     lib.ds_group_sync.argtypes = [vp, vp, i32, i64, i64, i64, i32, i32p, i32p, i32, ctypes.c_float, vp]
     lib.ds_ragged_plan_bytes.restype = sz
     lib.ds_ragged_plan_bytes.argtypes = [segp, i32]
     lib.ds_ragged_plan.restype = ctypes.c_int
-    lib.ds_ragged_plan.argtypes = [segp, i32, i64, i64, vp, sz, vp]
+    lib.ds_ragged_plan.argtypes = [segp, i32, i64, i64, vp, sz, ctypes.POINTER(u64), vp]
     lib.ds_group_sync_ragged.restype = ctypes.c_int
     lib.ds_group_sync_ragged.argtypes = [vp, vp, i32, segp, i32, i64, i64, i32, i32p, i32p, i32,
-                                         ctypes.c_float, vp, sz, vp]
+                                         ctypes.c_float, vp, sz, u64, vp]
     optp = ctypes.POINTER(ds_local_opt)
     lib.ds_group_sync_opt.restype = ctypes.c_int
     lib.ds_group_sync_opt.argtypes = [vp, vp, i32, i64, i64, i64, i32, i32p, i32p, i32, ctypes.c_float, optp, vp]
     lib.ds_group_sync_ragged_opt.restype = ctypes.c_int
     lib.ds_group_sync_ragged_opt.argtypes = [vp, vp, i32, segp, i32, i64, i64, i32, i32p, i32p, i32,
-                                             ctypes.c_float, optp, vp, sz, vp]
+                                             ctypes.c_float, optp, vp, sz, u64, vp]
     lib.ds_consensus_workspace_bytes.restype = sz
     lib.ds_consensus_workspace_bytes.argtypes = [i32, i64]
     lib.ds_consensus.restype = ctypes.c_int
@@ -80,8 +87,6 @@ def _load() -> ctypes.CDLL:
     lib.ds_consensus_grouped.argtypes = [vp, i64, i64, i32, i32p, i32p, i32, vp, vp, sz, vp]
     lib.ds_padded_ld.restype = i64
     lib.ds_padded_ld.argtypes = [i64]
-    lib.ds_probe_copy.restype = ctypes.c_int
-    lib.ds_probe_copy.argtypes = [vp, vp, sz, vp]
     return lib
 
 
@@ -192,6 +197,27 @@ def ds_pattern_period(rack_of: Sequence[int], slow_rack: Sequence[int], slow_wor
     return int(B.value)
 
 
+def ds_pattern_check(W: int, divisions) -> Tuple[bool, float, float]:
+    """``(connected, rho, sigma)`` of a periodic list of divisions, each a ``(perm, off)`` pair."""
+    divisions = list(divisions)
+    B = len(divisions)
+    perms = np.zeros((max(B, 1), max(W, 1)), dtype=np.int32)
+    offs = np.zeros((max(B, 1), max(W, 1) + 1), dtype=np.int32)
+    counts = np.zeros(max(B, 1), dtype=np.int32)
+    for k, (perm, off) in enumerate(divisions):
+        perm, off = _i32(perm), _i32(off)
+        if len(perm) != W or not 2 <= len(off) <= W + 1:
+            raise ValueError("division %d does not have W workers" % k)
+        perms[k, :W] = perm
+        offs[k, :len(off)] = off
+        counts[k] = len(off) - 1
+    connected = ctypes.c_int32(0)
+    rho, sigma = ctypes.c_double(0.0), ctypes.c_double(0.0)
+    _check(_lib.ds_pattern_check(int(W), B, _i32p(perms), _i32p(offs), _i32p(counts), ctypes.byref(connected),
+                                 ctypes.byref(rho), ctypes.byref(sigma)), "ds_pattern_check")
+    return bool(connected.value), float(rho.value), float(sigma.value)
+
+
 def ds_group_sync(X, G, g_dtype: int, P: int, ldx: int, ldg: int, W: int, perm, off, lr: float,
                   stream=None) -> None:
     perm, off = _i32(perm), _i32(off)
@@ -204,17 +230,21 @@ def ds_ragged_plan_bytes(segments) -> int:
     return int(_lib.ds_ragged_plan_bytes(arr, S))
 
 
-def ds_ragged_plan(segments, ldx: int, ldg: int, plan, plan_bytes: int, stream=None) -> None:
-    arr, S = _segs(segments)
-    _check(_lib.ds_ragged_plan(arr, S, ldx, ldg, _addr(plan), plan_bytes, _stream(stream)), "ds_ragged_plan")
+def ds_ragged_plan(segments, ldx: int, ldg: int, plan, plan_bytes: int, stream=None) -> int:
+    """Enqueues the kernels that write the plan; returns ``plan_id`` (what ``*plan_id_out`` received)."""
+    arr, S = segments if isinstance(segments, tuple) and isinstance(segments[1], int) else _segs(segments)
+    plan_id = ctypes.c_uint64(0)
+    _check(_lib.ds_ragged_plan(arr, S, ldx, ldg, _addr(plan), plan_bytes, ctypes.byref(plan_id), _stream(stream)),
+           "ds_ragged_plan")
+    return int(plan_id.value)
 
 
 def ds_group_sync_ragged(X, G, g_dtype: int, segments, ldx: int, ldg: int, W: int, perm, off, lr: float,
-                         plan, plan_bytes: int, stream=None) -> None:
+                         plan, plan_bytes: int, plan_id: int, stream=None) -> None:
     arr, S = segments if isinstance(segments, tuple) and isinstance(segments[1], int) else _segs(segments)
     perm, off = _i32(perm), _i32(off)
     _check(_lib.ds_group_sync_ragged(_addr(X), _addr(G), g_dtype, arr, S, ldx, ldg, W, _i32p(perm), _i32p(off),
-                                     len(off) - 1, lr, _addr(plan), plan_bytes, _stream(stream)),
+                                     len(off) - 1, lr, _addr(plan), plan_bytes, plan_id, _stream(stream)),
            "ds_group_sync_ragged")
 
 
@@ -233,12 +263,13 @@ def ds_group_sync_opt(X, G, g_dtype: int, P: int, ldx: int, ldg: int, W: int, pe
 
 
 def ds_group_sync_ragged_opt(X, G, g_dtype: int, segments, ldx: int, ldg: int, W: int, perm, off, lr: float,
-                             opt: ds_local_opt | None, plan, plan_bytes: int, stream=None) -> None:
+                             opt: ds_local_opt | None, plan, plan_bytes: int, plan_id: int, stream=None) -> None:
     arr, S = segments if isinstance(segments, tuple) and isinstance(segments[1], int) else _segs(segments)
     perm, off = _i32(perm), _i32(off)
     _check(_lib.ds_group_sync_ragged_opt(_addr(X), _addr(G), g_dtype, arr, S, ldx, ldg, W, _i32p(perm), _i32p(off),
                                          len(off) - 1, lr, ctypes.byref(opt) if opt is not None else None,
-                                         _addr(plan), plan_bytes, _stream(stream)), "ds_group_sync_ragged_opt")
+                                         _addr(plan), plan_bytes, plan_id, _stream(stream)),
+           "ds_group_sync_ragged_opt")
 
 
 def pack_segments(segments):
@@ -264,7 +295,3 @@ def ds_consensus_grouped(X, P: int, ld: int, W: int, perm, off, dev_out, workspa
 
 def ds_padded_ld(P: int) -> int:
     return int(_lib.ds_padded_ld(int(P)))
-
-
-def ds_probe_copy(dst, src, nbytes: int, stream=None) -> None:
-    _check(_lib.ds_probe_copy(_addr(dst), _addr(src), nbytes, _stream(stream)), "ds_probe_copy")

@@ -15,7 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdssync.so")
-SOURCES = ["partition.cpp", "pattern.cpp", "group_sync.hip", "consensus.hip", "probe.hip"]
+SOURCES = ["partition.cpp", "pattern.cpp", "device_info.hip", "group_sync.hip", "consensus.hip"]
 
 
 def hipcc() -> str:
@@ -25,14 +25,15 @@ def hipcc() -> str:
     return exe
 
 
-def build_library(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
+def compile_shared(sources, out: str, verbose: bool = False, extra_flags=()) -> str:
+    """hipcc, gfx950 only, one shared object from the given sources."""
     cmd = [hipcc(), "-x", "hip", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            "-Wall", "-Wno-unused-command-line-argument",
            # packed fp32 instructions are kept out of the generated code on purpose
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-I", os.path.join(ROOT, "include"), "-I", CSRC]
     cmd += list(extra_flags)
-    cmd += [os.path.join(CSRC, s) for s in SOURCES]
+    cmd += list(sources)
     cmd += ["-o", out]
     if verbose:
         print(" ".join(cmd), flush=True)
@@ -44,6 +45,10 @@ def build_library(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
     if verbose and err.strip():
         print(err, file=sys.stderr)
     return out
+
+
+def build_library(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
+    return compile_shared([os.path.join(CSRC, s) for s in SOURCES], out, verbose, extra_flags)
 
 
 if __name__ == "__main__":

@@ -11,21 +11,26 @@
 //     error is relative to the difference itself (and exactly zero for
 //     identical replicas); it is squared and summed into one fp32 accumulator
 //     per worker per lane;
-//   - a workgroup walks a run of consecutive column tiles; at the end the lane
-//     accumulators are widened to fp64, reduced across the wavefront with
-//     lane shuffles, across the 4 wavefronts through LDS, and written as one
-//     partial row per workgroup;
+//   - a workgroup walks a run of consecutive column tiles; after every
+//     kFlushTiles tiles (and at the end) the lane accumulators are widened to
+//     fp64, reduced across the wavefront with lane shuffles and added to the
+//     wavefront's fp64 totals in LDS, so an fp32 accumulator never holds more
+//     than kFlushTiles * kVec <= 128 squares and the rounding error of a norm
+//     does not grow with the number of columns; at the end the 4 wavefronts'
+//     totals are added and written as one partial row per workgroup;
 //   - a second kernel adds the partial rows in a fixed order and takes the
 //     square root.  No floating-point atomics: the result is deterministic.
 #include <hip/hip_runtime.h>
 
 #include "ds_internal.h"
+#include "launch.h"
 
 namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
 constexpr int kMaxBlocks = 8192;  // upper bound of the grid of the partial kernel
+constexpr int kFlushTiles = 32;   // tiles between two widenings of the fp32 lane accumulators
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
@@ -125,10 +130,17 @@ consensus_partial_kernel(const float* __restrict__ X, int64_t P, int64_t ld, int
 #pragma unroll
     for (int i = 0; i < kWPad; ++i) acc[i] = 0.f;
 
+    __shared__ double wave_sum[kWaves][kWPad];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    static_assert(kWPad <= 64, "one lane per worker clears the wavefront's totals");
+    if (lane < kWPad) wave_sum[wave][lane] = 0.0;   // only this wavefront touches its row before the barrier
+
     // a workgroup owns tiles_per_block consecutive tiles
     const int64_t n_tiles = (P + kTileCols - 1) / kTileCols;
     const int64_t tile0 = static_cast<int64_t>(blockIdx.x) * tiles_per_block;
     const int64_t tile1 = tile0 + tiles_per_block < n_tiles ? tile0 + tiles_per_block : n_tiles;
+    int since = 0;
     for (int64_t tile = tile0; tile < tile1; ++tile) {
         const int64_t c = tile * kTileCols + static_cast<int64_t>(threadIdx.x) * kVec;
         if ((tile + 1) * kTileCols <= P) {
@@ -139,19 +151,21 @@ consensus_partial_kernel(const float* __restrict__ X, int64_t P, int64_t ld, int
             else
                 consensus_tile<kWPad, kVec, false, kGrouped>(acc, X, c, P, ld, W, tab, total_weight);
         }
+        if (++since == kFlushTiles || tile + 1 == tile1) {
+            // lanes -> wavefront in fp64, added to the wavefront's totals; the fp32 sums start over
+            since = 0;
+#pragma unroll
+            for (int i = 0; i < kWPad; ++i) {
+                double v = static_cast<double>(acc[i]);
+#pragma unroll
+                for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+                if (lane == 0) wave_sum[wave][i] += v;
+                acc[i] = 0.f;
+            }
+        }
     }
 
-    // lanes -> wavefront (fp32 butterfly) -> workgroup -> partial row (fp64)
-    __shared__ double wave_sum[kWaves][kWPad];
-    const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
-#pragma unroll
-    for (int i = 0; i < kWPad; ++i) {
-        double v = static_cast<double>(acc[i]);
-#pragma unroll
-        for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
-        if (lane == 0) wave_sum[wave][i] = v;
-    }
+    // wavefronts -> workgroup -> partial row
     __syncthreads();
     if (threadIdx.x < kWPad) {
         double v = 0.0;
@@ -208,23 +222,24 @@ int launch_consensus(const float* x, int64_t P, int64_t ld, int32_t W, int32_t n
     const int n_blocks = static_cast<int>(want_blocks < 1 ? 1 : want_blocks);
     const int tpb = static_cast<int>(per_block);
     const dim3 grid(static_cast<uint32_t>(n_blocks)), block(kThreads);
+    hipError_t err;
     switch (w_pad) {
-        case 8: hipLaunchKernelGGL((consensus_partial_kernel<8, 4, kGrouped>), grid, block, 0, st, x, P, ld, n_rows, tpb, partial, tab, W); break;
-        case 16: hipLaunchKernelGGL((consensus_partial_kernel<16, 4, kGrouped>), grid, block, 0, st, x, P, ld, n_rows, tpb, partial, tab, W); break;
-        case 32: hipLaunchKernelGGL((consensus_partial_kernel<32, 2, kGrouped>), grid, block, 0, st, x, P, ld, n_rows, tpb, partial, tab, W); break;
-        default: hipLaunchKernelGGL((consensus_partial_kernel<64, 2, kGrouped>), grid, block, 0, st, x, P, ld, n_rows, tpb, partial, tab, W); break;
+        case 8: err = ds::launch_kernel(consensus_partial_kernel<8, 4, kGrouped>, grid, block, 0, st, x, P, ld, n_rows, tpb, partial, tab, W); break;
+        case 16: err = ds::launch_kernel(consensus_partial_kernel<16, 4, kGrouped>, grid, block, 0, st, x, P, ld, n_rows, tpb, partial, tab, W); break;
+        case 32: err = ds::launch_kernel(consensus_partial_kernel<32, 2, kGrouped>, grid, block, 0, st, x, P, ld, n_rows, tpb, partial, tab, W); break;
+        default: err = ds::launch_kernel(consensus_partial_kernel<64, 2, kGrouped>, grid, block, 0, st, x, P, ld, n_rows, tpb, partial, tab, W); break;
     }
-    if (hipGetLastError() != hipSuccess) return DS_ERR_HIP;
-    hipLaunchKernelGGL(consensus_final_kernel, dim3(static_cast<uint32_t>(W)), block, 0, st, partial, n_blocks, w_pad,
-                       dev_out, tab);
-    return hipGetLastError() == hipSuccess ? DS_OK : DS_ERR_HIP;
+    if (err != hipSuccess) return DS_ERR_HIP;
+    err = ds::launch_kernel(consensus_final_kernel, dim3(static_cast<uint32_t>(W)), block, 0, st, partial, n_blocks, w_pad,
+                            dev_out, tab);
+    return err == hipSuccess ? DS_OK : DS_ERR_HIP;
 }
 
 int check_consensus_args(const void* X, int64_t P, int64_t ld, int32_t W, const double* dev_out, const void* workspace,
                          size_t workspace_bytes) {
     if (!X || !dev_out) return DS_ERR_NULL;
     if (W < 1 || W > DS_MAX_W) return DS_ERR_BAD_W;
-    if (P < 0 || ld < P) return DS_ERR_BAD_SHAPE;
+    if (P < 0 || ld < P || P > DS_MAX_COLUMNS) return DS_ERR_BAD_SHAPE;
     if (!ds::aligned16(X) || ld % 4 != 0 || (reinterpret_cast<uintptr_t>(dev_out) & 7u) != 0) return DS_ERR_ALIGN;
     if (!workspace || !ds::aligned16(workspace) || workspace_bytes < ds_consensus_workspace_bytes(W, P))
         return DS_ERR_WORKSPACE;
@@ -249,8 +264,8 @@ extern "C" int ds_consensus_grouped(const void* X, int64_t P, int64_t ld, int32_
     const int rc = check_consensus_args(X, P, ld, W, dev_out, workspace, workspace_bytes);
     if (rc != DS_OK) return rc;
     ds::PartitionArg packed;
-    int32_t max_size = 0, equal_size = 0;
-    const int prc = ds::pack_partition(W, perm, off, n_groups, &packed, &max_size, &equal_size);
+    int32_t max_size = 0;
+    const int prc = ds::pack_partition(W, perm, off, n_groups, &packed, &max_size);
     if (prc != DS_OK) return prc;
     RowTable tab = {};
     for (int32_t k = 0; k < n_groups; ++k) {

@@ -20,12 +20,20 @@ struct PartitionArg {
 
 
 // Checks perm/off (host arrays) and packs them; returns DS_OK or the status to
-// hand back to the caller.  max_size receives the largest group size and
-// equal_size the common size if all groups are equal (else 0).
+// hand back to the caller.  max_size receives the largest group size.
 int pack_partition(int32_t W, const int32_t* perm, const int32_t* off, int32_t n_groups,
-                   PartitionArg* out, int32_t* max_size, int32_t* equal_size);
+                   PartitionArg* out, int32_t* max_size);
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// What the launch rules need to know of the current device.  Read with
+// hipDeviceGetAttribute on the first launch on a device and kept for the
+// life of the process (no allocation).  Returns DS_OK or DS_ERR_HIP.
+struct DeviceInfo {
+    int compute_units;
+    unsigned lds_per_cu;   // bytes
+};
+int device_info(DeviceInfo* out);
 
 // Group-sync launch shape.  A workgroup is ONE wavefront; a lane owns one
 // vector of 4 consecutive columns, so a workgroup covers 256 columns of every
@@ -37,6 +45,10 @@ constexpr int kSyncLoadsPerLane = 16;
 // Unit of the ragged plan: 2048 columns = 8 workgroups.
 constexpr int kPlanTileCols = 2048;
 
+// HIP refuses a launch whose gridDim.x * blockDim.x reaches 2^32; with
+// one-wavefront workgroups that is 2^26 workgroups along x.
+constexpr int64_t kMaxSyncGridX = (int64_t{1} << 32) / kSyncThreads - 1;
+
 // One entry of the ragged plan: a run of at most kPlanTileCols columns that
 // lies inside one segment and starts on a multiple of 8 columns.
 struct Tile {
@@ -44,5 +56,14 @@ struct Tile {
     int32_t len;
     int32_t pad;
 };
+
+// Entry 0 of a plan buffer: says which segment list the entries after it were
+// cut from, so that a launch can tell a plan that belongs to another list.
+struct PlanHeader {
+    uint64_t id;        // ds_ragged_plan's plan_id_out: hash of the list, never 0
+    int32_t n_segments;
+    int32_t n_entries;  // Tile entries that follow
+};
+static_assert(sizeof(PlanHeader) == sizeof(Tile), "the header takes the place of one entry");
 
 }  // namespace ds

@@ -62,6 +62,7 @@
 #include <vector>
 
 #include "ds_internal.h"
+#include "launch.h"
 
 namespace {
 
@@ -70,27 +71,28 @@ using ds::kSyncLoadsPerLane;
 using ds::kSyncTileCols;
 using ds::kSyncThreads;
 using ds::PartitionArg;
+using ds::PlanHeader;
 using ds::Tile;
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 // Occupancy cap.  The launch requests dynamic LDS that the kernel never touches, so
-// that only floor(160 KiB / request) one-wavefront workgroups fit a CU.  The
+// that only floor(LDS per CU / request) one-wavefront workgroups fit a CU (160 KiB
+// on MI355X; the figure is read from the device).  The
 // number aimed for keeps about 80 KiB of first-round loads in flight per CU
 // (with bf16 gradients 60 KiB for pairs rising to 72 KiB for groups of 8):
 // measured on MI355X over group sizes 1..8, fp32 and bf16 gradients, with and
 // without the momentum and SWA buffers, the best cap was within 3.5 % of this
 // rule everywhere (e.g. 16 KiB per wavefront -> 5 per CU, 8 KiB -> 10,
 // 4 KiB -> 20, 24 KiB -> 3).
-constexpr unsigned kLdsPerCu = 160u * 1024u;
 constexpr unsigned kLdsGranule = 2048;
 constexpr int kInFlightHalfKiB = 160;        // fp32 gradients
 constexpr int kInFlightHalfKiBBf16 = 112;    // bf16 gradients: this plus 4 per member of a round ...
 constexpr int kInFlightHalfKiBBf16V = 144;   // ... or this with the momentum buffer
 constexpr int kMinWavesPerCu = 3;
 constexpr int kUncappedWavesPerCu = 26;      // from here on the register file is the limit anyway
-constexpr int64_t kUncappedWorkgroups = 256 * 32;   // one full-occupancy load of the 256 CUs
+constexpr int kUncappedWorkgroupsPerCu = 32;   // a launch of up to this many per CU fits the chip in one go
 
 template <typename V>
 __device__ __forceinline__ V stream_load(const V* p) { return __builtin_nontemporal_load(p); }
@@ -259,7 +261,8 @@ __device__ __forceinline__ void sync_tile(float* xt, const GT* gt, int len, int6
 template <typename GT, bool kRagged, bool kOpt, bool kHasV, bool kHasS>
 __global__ void __launch_bounds__(kSyncThreads)
 group_sync_kernel(float* __restrict__ X, const GT* __restrict__ G, int64_t ldx, int64_t ldg,
-                  int64_t P, const Tile* __restrict__ tiles, PartitionArg part, float lr, Extras ex) {
+                  int64_t P, const Tile* __restrict__ tiles, uint64_t plan_id, int32_t plan_entries,
+                  PartitionArg part, float lr, Extras ex) {
     static_assert(kOpt || (!kHasV && !kHasS), "extra state implies the extended step");
     constexpr int kTileCols = kSyncTileCols;
     const uint32_t tile_id = blockIdx.x, group_id = blockIdx.y;
@@ -268,7 +271,10 @@ group_sync_kernel(float* __restrict__ X, const GT* __restrict__ G, int64_t ldx, 
     if (kRagged) {
         // a plan entry covers up to kPlanTileCols columns: kSub workgroups share it
         constexpr uint32_t kSub = kPlanTileCols / kTileCols;
-        const Tile tl = tiles[tile_id / kSub];
+        // entry 0 says which plan this is: a buffer that holds another plan (or none) is left alone
+        const PlanHeader hd = *reinterpret_cast<const PlanHeader*>(tiles);
+        if (hd.id != plan_id || hd.n_entries != plan_entries) return;
+        const Tile tl = tiles[1 + tile_id / kSub];
         const int32_t done = static_cast<int32_t>(tile_id % kSub) * kTileCols;
         // a table that does not belong to these stacks must not become a wild access
         int64_t ld_min = ldx < ldg ? ldx : ldg;
@@ -294,38 +300,96 @@ group_sync_kernel(float* __restrict__ X, const GT* __restrict__ G, int64_t ldx, 
         sync_tile<GT, false, kOpt, kHasV, kHasS>(X + start, G + start, len, ldx, ldg, ex, part, first, n, lr);
 }
 
+// ---------------------------------------------------------------- ragged plan
+
+// Segments handed to one launch of the plan kernel, inside its kernel-argument
+// block: the table is written on the device from arguments alone, so building
+// a plan needs no host-to-device copy and no wait.
+constexpr int kPlanBatch = 96;
+struct PlanBatch {
+    int64_t offset[kPlanBatch];
+    int64_t length[kPlanBatch];
+    int64_t first_entry[kPlanBatch];   // position of the segment's first entry among all entries
+    int32_t count;
+    int32_t with_header;               // this launch also writes entry 0
+    PlanHeader header;
+};
+constexpr int kPlanThreads = 256;
+
+// One workgroup per segment of the batch: entry k of the segment covers its
+// columns k*kPlanTileCols .. and is written by thread k mod 256.
+__global__ void __launch_bounds__(kPlanThreads) plan_fill_kernel(Tile* __restrict__ plan, PlanBatch b) {
+    const int s = static_cast<int>(blockIdx.x);
+    if (b.with_header && s == 0 && threadIdx.x == 0) *reinterpret_cast<PlanHeader*>(plan) = b.header;
+    const int64_t off = b.offset[s], len = b.length[s];
+    const int64_t n = (len + kPlanTileCols - 1) / kPlanTileCols;
+    Tile* out = plan + 1 + b.first_entry[s];
+    for (int64_t k = threadIdx.x; k < n; k += kPlanThreads) {
+        const int64_t done = k * kPlanTileCols;
+        const int64_t left = len - done;
+        Tile tl;
+        tl.start = off + done;
+        tl.len = static_cast<int32_t>(left < kPlanTileCols ? left : kPlanTileCols);
+        tl.pad = 0;
+        out[k] = tl;
+    }
+}
+
 struct SegmentScan {
     int status;
-    int64_t n_tiles;
+    int64_t n_entries;     // plan entries (runs of up to kPlanTileCols columns)
+    int64_t n_live_tiles;  // workgroups that find columns to process
+    int64_t end;           // one past the last column of any segment
+    uint64_t id;           // identity of the list: 0 if it has no columns
 };
 
-// Validates a segment list and counts the tiles it is cut into.
-SegmentScan scan_segments(const ds_segment* segs, int32_t S, int64_t ldx, int64_t ldg, bool have_ld) {
-    if (S < 0) return {DS_ERR_BAD_SHAPE, 0};
-    if (S > 0 && !segs) return {DS_ERR_NULL, 0};
-    int64_t tiles = 0;
-    for (int32_t s = 0; s < S; ++s) {
-        const int64_t o = segs[s].offset, l = segs[s].length;
-        if (o < 0 || l < 0 || l > INT64_MAX - o) return {DS_ERR_BAD_SHAPE, 0};
-        if (o % 8 != 0) return {DS_ERR_ALIGN, 0};
-        if (have_ld && (o + l > ldx || o + l > ldg)) return {DS_ERR_BAD_SHAPE, 0};
-        tiles += (l + kPlanTileCols - 1) / kPlanTileCols;
-        if (tiles > INT32_MAX / 8) return {DS_ERR_BAD_SHAPE, 0};   // up to 8 workgroups per entry
-    }
-    return {DS_OK, tiles};
+inline uint64_t fold(uint64_t h, uint64_t word) {
+    h = (h ^ word) * 0x100000001B3ull;   // FNV-1a step on a whole word ...
+    return h ^ (h >> 29);                // ... with the high bits folded back
 }
 
-// Pairwise disjointness of the non-empty segments (sort by offset, compare neighbours).
-bool segments_overlap(const ds_segment* segs, int32_t S) {
-    std::vector<std::pair<int64_t, int64_t>> v;
-    v.reserve(static_cast<size_t>(S));
-    for (int32_t s = 0; s < S; ++s)
-        if (segs[s].length > 0) v.emplace_back(segs[s].offset, segs[s].offset + segs[s].length);
-    std::sort(v.begin(), v.end());
-    for (size_t i = 1; i < v.size(); ++i)
-        if (v[i].first < v[i - 1].second) return true;
-    return false;
+// Validates a segment list, counts the entries it is cut into and fingerprints it.
+SegmentScan scan_segments(const ds_segment* segs, int32_t S, int64_t ldx, int64_t ldg, bool have_ld) {
+    SegmentScan sc = {DS_OK, 0, 0, 0, 0};
+    if (S < 0) return {DS_ERR_BAD_SHAPE, 0, 0, 0, 0};
+    if (S > 0 && !segs) return {DS_ERR_NULL, 0, 0, 0, 0};
+    uint64_t h = fold(0xCBF29CE484222325ull, static_cast<uint64_t>(S));
+    for (int32_t s = 0; s < S; ++s) {
+        const int64_t o = segs[s].offset, l = segs[s].length;
+        if (o < 0 || l < 0 || l > INT64_MAX - o) return {DS_ERR_BAD_SHAPE, 0, 0, 0, 0};
+        if (o % 8 != 0) return {DS_ERR_ALIGN, 0, 0, 0, 0};
+        if (have_ld && (o + l > ldx || o + l > ldg)) return {DS_ERR_BAD_SHAPE, 0, 0, 0, 0};
+        // bounded before it is added, so the sums below cannot overflow
+        if (l > DS_MAX_COLUMNS) return {DS_ERR_BAD_SHAPE, 0, 0, 0, 0};
+        sc.n_entries += (l + kPlanTileCols - 1) / kPlanTileCols;
+        sc.n_live_tiles += (l + kSyncTileCols - 1) / kSyncTileCols;
+        // every entry is launched as kPlanTileCols / kSyncTileCols workgroups along x
+        if (sc.n_entries * (kPlanTileCols / kSyncTileCols) > ds::kMaxSyncGridX) return {DS_ERR_BAD_SHAPE, 0, 0, 0, 0};
+        if (o + l > sc.end) sc.end = o + l;
+        h = fold(fold(h, static_cast<uint64_t>(o)), static_cast<uint64_t>(l));
+    }
+    sc.id = sc.n_entries == 0 ? 0 : (h != 0 ? h : 1);
+    return sc;
 }
+
+// Pairwise disjointness of the non-empty segments (sort by offset, compare
+// neighbours).  DS_OK, DS_ERR_BAD_SHAPE for an overlap, DS_ERR_HOST_MEMORY.
+int check_disjoint(const ds_segment* segs, int32_t S) {
+    try {
+        std::vector<std::pair<int64_t, int64_t>> v;
+        v.reserve(static_cast<size_t>(S));
+        for (int32_t s = 0; s < S; ++s)
+            if (segs[s].length > 0) v.emplace_back(segs[s].offset, segs[s].offset + segs[s].length);
+        std::sort(v.begin(), v.end());
+        for (size_t i = 1; i < v.size(); ++i)
+            if (v[i].first < v[i - 1].second) return DS_ERR_BAD_SHAPE;
+    } catch (...) {
+        return DS_ERR_HOST_MEMORY;
+    }
+    return DS_OK;
+}
+
+// ---------------------------------------------------------------- launch
 
 int check_stacks(const void* X, const void* G, int32_t g_dtype, int64_t ldx, int64_t ldg) {
     if (!X || !G) return DS_ERR_NULL;
@@ -338,61 +402,67 @@ int check_stacks(const void* X, const void* G, int32_t g_dtype, int64_t ldx, int
 // Dynamic LDS request (bytes) for a division whose largest group has `largest`
 // members.  A round loads min(largest, 8) members, each 1 KiB of x, 1 KiB (fp32)
 // or 0.5 KiB (bf16) of g and, with momentum, 1 KiB of v per wavefront; the SWA
-// rows are loaded in a later round and do not count.
-unsigned occupancy_pad(int32_t largest, bool bf16, bool has_v, int64_t n_workgroups) {
+// rows are loaded in a later round and do not count.  n_workgroups counts the
+// workgroups that have columns to process.
+unsigned occupancy_pad(int32_t largest, bool bf16, bool has_v, int64_t n_workgroups, const ds::DeviceInfo& dev) {
     // a launch that fits the chip in one go (cache-resident, latency-bound) is better off uncapped
-    if (n_workgroups <= kUncappedWorkgroups) return 0;
+    if (n_workgroups <= static_cast<int64_t>(dev.compute_units) * kUncappedWorkgroupsPerCu) return 0;
     const int round = largest < kSyncLoadsPerLane / 2 ? largest : kSyncLoadsPerLane / 2;
     const int half_kib = round * (2 + (bf16 ? 1 : 2) + (has_v ? 2 : 0));
     const int target = !bf16 ? kInFlightHalfKiB : has_v ? kInFlightHalfKiBBf16V : kInFlightHalfKiBBf16 + 4 * round;
     int waves = target / half_kib;
     if (waves < kMinWavesPerCu) waves = kMinWavesPerCu;
     if (waves >= kUncappedWavesPerCu) return 0;
-    return kLdsPerCu / static_cast<unsigned>(waves) / kLdsGranule * kLdsGranule;
+    return dev.lds_per_cu / static_cast<unsigned>(waves) / kLdsGranule * kLdsGranule;
 }
 
+// What a launch needs beyond the stacks.
+struct LaunchShape {
+    int64_t P;               // flat: columns
+    const Tile* plan;        // ragged: plan buffer (header + entries), else NULL
+    uint64_t plan_id;
+    int64_t plan_entries;
+    int64_t n_live_tiles;    // workgroups along x that find columns
+    int32_t largest;         // largest group
+    int32_t n_groups;
+};
+
 template <typename GT, bool kRagged, bool kOpt, bool kHasV, bool kHasS>
-void launch_one(float* X, const GT* G, int64_t P, int64_t ldx, int64_t ldg, int64_t n_units, const Tile* tiles,
-                const PartitionArg& part, int32_t largest, int32_t n_groups, float lr, const Extras& ex,
-                hipStream_t st) {
-    // n_units: flat -> columns; ragged -> plan entries
-    constexpr int kTileCols = kSyncTileCols;
-    const int64_t n_tiles = kRagged ? n_units * (kPlanTileCols / kTileCols) : (n_units + kTileCols - 1) / kTileCols;
-    const dim3 grid(static_cast<uint32_t>(n_tiles), static_cast<uint32_t>(n_groups), 1);
-    const unsigned lds_pad = occupancy_pad(largest, sizeof(GT) == 2, kHasV, n_tiles * n_groups);
-    hipLaunchKernelGGL((group_sync_kernel<GT, kRagged, kOpt, kHasV, kHasS>), grid, dim3(kSyncThreads, 1, 1),
-                       lds_pad, st, X, G, ldx, ldg, P, tiles, part, lr, ex);
+int launch_one(float* X, const GT* G, int64_t ldx, int64_t ldg, const LaunchShape& sh, const PartitionArg& part,
+               float lr, const Extras& ex, hipStream_t st) {
+    ds::DeviceInfo dev;
+    const int rc = ds::device_info(&dev);
+    if (rc != DS_OK) return rc;
+    const int64_t grid_x = kRagged ? sh.plan_entries * (kPlanTileCols / kSyncTileCols)
+                                   : (sh.P + kSyncTileCols - 1) / kSyncTileCols;
+    const dim3 grid(static_cast<uint32_t>(grid_x), static_cast<uint32_t>(sh.n_groups), 1);
+    const unsigned lds_pad = occupancy_pad(sh.largest, sizeof(GT) == 2, kHasV, sh.n_live_tiles * sh.n_groups, dev);
+    const hipError_t err = ds::launch_kernel(group_sync_kernel<GT, kRagged, kOpt, kHasV, kHasS>, grid,
+                                             dim3(kSyncThreads, 1, 1), lds_pad, st, X, G, ldx, ldg, sh.P, sh.plan,
+                                             sh.plan_id, static_cast<int32_t>(sh.plan_entries), part, lr, ex);
+    return err == hipSuccess ? DS_OK : DS_ERR_HIP;
 }
 
 template <typename GT, bool kRagged>
-void launch_state(int32_t largest, float* X, const GT* G, int64_t P, int64_t ldx, int64_t ldg, int64_t n_units,
-                  const Tile* tiles, const PartitionArg& part, int32_t n_groups, float lr, bool opt, const Extras& ex,
-                  hipStream_t st) {
+int launch_state(float* X, const GT* G, int64_t ldx, int64_t ldg, const LaunchShape& sh, const PartitionArg& part,
+                 float lr, bool opt, const Extras& ex, hipStream_t st) {
     const bool has_v = ex.v != nullptr, has_s = ex.s != nullptr;
-    if (!opt)
-        launch_one<GT, kRagged, false, false, false>(X, G, P, ldx, ldg, n_units, tiles, part, largest, n_groups, lr, ex, st);
-    else if (has_v && has_s)
-        launch_one<GT, kRagged, true, true, true>(X, G, P, ldx, ldg, n_units, tiles, part, largest, n_groups, lr, ex, st);
-    else if (has_v)
-        launch_one<GT, kRagged, true, true, false>(X, G, P, ldx, ldg, n_units, tiles, part, largest, n_groups, lr, ex, st);
-    else if (has_s)
-        launch_one<GT, kRagged, true, false, true>(X, G, P, ldx, ldg, n_units, tiles, part, largest, n_groups, lr, ex, st);
-    else
-        launch_one<GT, kRagged, true, false, false>(X, G, P, ldx, ldg, n_units, tiles, part, largest, n_groups, lr, ex, st);
+    if (!opt) return launch_one<GT, kRagged, false, false, false>(X, G, ldx, ldg, sh, part, lr, ex, st);
+    if (has_v && has_s) return launch_one<GT, kRagged, true, true, true>(X, G, ldx, ldg, sh, part, lr, ex, st);
+    if (has_v) return launch_one<GT, kRagged, true, true, false>(X, G, ldx, ldg, sh, part, lr, ex, st);
+    if (has_s) return launch_one<GT, kRagged, true, false, true>(X, G, ldx, ldg, sh, part, lr, ex, st);
+    return launch_one<GT, kRagged, true, false, false>(X, G, ldx, ldg, sh, part, lr, ex, st);
 }
 
 template <bool kRagged>
-int launch(void* X, const void* G, int32_t g_dtype, int64_t P, int64_t ldx, int64_t ldg, int64_t n_units,
-           const Tile* tiles, const PartitionArg& part, int32_t largest, int32_t n_groups, float lr, bool opt,
-           const Extras& ex, void* stream) {
+int launch(void* X, const void* G, int32_t g_dtype, int64_t ldx, int64_t ldg, const LaunchShape& sh,
+           const PartitionArg& part, float lr, bool opt, const Extras& ex, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (g_dtype == DS_F32)
-        launch_state<float, kRagged>(largest, static_cast<float*>(X), static_cast<const float*>(G), P, ldx, ldg, n_units,
-                                     tiles, part, n_groups, lr, opt, ex, st);
-    else
-        launch_state<uint16_t, kRagged>(largest, static_cast<float*>(X), static_cast<const uint16_t*>(G), P, ldx, ldg,
-                                        n_units, tiles, part, n_groups, lr, opt, ex, st);
-    return hipGetLastError() == hipSuccess ? DS_OK : DS_ERR_HIP;
+        return launch_state<float, kRagged>(static_cast<float*>(X), static_cast<const float*>(G), ldx, ldg, sh, part,
+                                            lr, opt, ex, st);
+    return launch_state<uint16_t, kRagged>(static_cast<float*>(X), static_cast<const uint16_t*>(G), ldx, ldg, sh, part,
+                                           lr, opt, ex, st);
 }
 
 // Checks the optional state of the extended step and turns it into kernel arguments.
@@ -420,51 +490,47 @@ int read_opt(const ds_local_opt* opt, int64_t min_ld, Extras* ex, bool* opt_out)
     return DS_OK;
 }
 
-int64_t segments_end(const ds_segment* segs, int32_t S) {
-    int64_t end = 0;
-    for (int32_t s = 0; s < S; ++s) end = std::max(end, segs[s].offset + segs[s].length);
-    return end;
-}
-
 int group_sync_flat(void* X, const void* G, int32_t g_dtype, int64_t P, int64_t ldx, int64_t ldg, int32_t W,
                     const int32_t* perm, const int32_t* off, int32_t n_groups, float lr, const ds_local_opt* opt,
                     void* stream) {
     int rc = check_stacks(X, G, g_dtype, ldx, ldg);
     if (rc != DS_OK) return rc;
-    if (P < 0 || ldx < P || ldg < P) return DS_ERR_BAD_SHAPE;
+    if (P < 0 || ldx < P || ldg < P || P > DS_MAX_COLUMNS) return DS_ERR_BAD_SHAPE;
     Extras ex;
     bool extended = false;
     rc = read_opt(opt, P, &ex, &extended);
     if (rc != DS_OK) return rc;
     PartitionArg part;
-    int32_t max_size = 0, equal_size = 0;
-    rc = ds::pack_partition(W, perm, off, n_groups, &part, &max_size, &equal_size);
+    int32_t max_size = 0;
+    rc = ds::pack_partition(W, perm, off, n_groups, &part, &max_size);
     if (rc != DS_OK) return rc;
-    if (P / kSyncTileCols >= INT32_MAX) return DS_ERR_BAD_SHAPE;   // grid.x limit
     if (P == 0) return DS_OK;
-    return launch<false>(X, G, g_dtype, P, ldx, ldg, P, nullptr, part, max_size, n_groups, lr, extended, ex, stream);
+    const LaunchShape sh = {P, nullptr, 0, 0, (P + kSyncTileCols - 1) / kSyncTileCols, max_size, n_groups};
+    return launch<false>(X, G, g_dtype, ldx, ldg, sh, part, lr, extended, ex, stream);
 }
 
 int group_sync_ragged(void* X, const void* G, int32_t g_dtype, const ds_segment* segs, int32_t S, int64_t ldx,
                       int64_t ldg, int32_t W, const int32_t* perm, const int32_t* off, int32_t n_groups, float lr,
-                      const ds_local_opt* opt, const void* plan, size_t plan_bytes, void* stream) {
+                      const ds_local_opt* opt, const void* plan, size_t plan_bytes, uint64_t plan_id, void* stream) {
     int rc = check_stacks(X, G, g_dtype, ldx, ldg);
     if (rc != DS_OK) return rc;
     const SegmentScan sc = scan_segments(segs, S, ldx, ldg, true);
     if (sc.status != DS_OK) return sc.status;
     Extras ex;
     bool extended = false;
-    rc = read_opt(opt, segments_end(segs, S), &ex, &extended);
+    rc = read_opt(opt, sc.end, &ex, &extended);
     if (rc != DS_OK) return rc;
     PartitionArg part;
-    int32_t max_size = 0, equal_size = 0;
-    rc = ds::pack_partition(W, perm, off, n_groups, &part, &max_size, &equal_size);
+    int32_t max_size = 0;
+    rc = ds::pack_partition(W, perm, off, n_groups, &part, &max_size);
     if (rc != DS_OK) return rc;
-    if (sc.n_tiles == 0) return DS_OK;
-    if (!plan || !ds::aligned16(plan) || plan_bytes < static_cast<size_t>(sc.n_tiles) * sizeof(Tile))
+    if (sc.n_entries == 0) return DS_OK;
+    if (!plan || !ds::aligned16(plan) || plan_bytes < static_cast<size_t>(sc.n_entries + 1) * sizeof(Tile))
         return DS_ERR_WORKSPACE;
-    return launch<true>(X, G, g_dtype, 0, ldx, ldg, sc.n_tiles, static_cast<const Tile*>(plan), part, max_size,
-                        n_groups, lr, extended, ex, stream);
+    if (plan_id != sc.id) return DS_ERR_WORKSPACE;   // the plan was built from another list
+    const LaunchShape sh = {0, static_cast<const Tile*>(plan), plan_id, sc.n_entries, sc.n_live_tiles, max_size,
+                            n_groups};
+    return launch<true>(X, G, g_dtype, ldx, ldg, sh, part, lr, extended, ex, stream);
 }
 
 }  // namespace
@@ -483,48 +549,59 @@ extern "C" int ds_group_sync_opt(void* X, const void* G, int32_t g_dtype, int64_
 
 extern "C" size_t ds_ragged_plan_bytes(const ds_segment* segs, int32_t S) {
     const SegmentScan sc = scan_segments(segs, S, 0, 0, false);
-    if (sc.status != DS_OK) return 0;
-    return static_cast<size_t>(sc.n_tiles) * sizeof(Tile);
+    if (sc.status != DS_OK || sc.n_entries == 0) return 0;
+    return static_cast<size_t>(sc.n_entries + 1) * sizeof(Tile);   // entry 0 is the header
 }
 
 extern "C" int ds_ragged_plan(const ds_segment* segs, int32_t S, int64_t ldx, int64_t ldg, void* plan,
-                              size_t plan_bytes, void* stream) {
+                              size_t plan_bytes, uint64_t* plan_id_out, void* stream) {
+    if (!plan_id_out) return DS_ERR_NULL;
+    *plan_id_out = 0;
     if (ldx < 0 || ldg < 0) return DS_ERR_BAD_SHAPE;
     const SegmentScan sc = scan_segments(segs, S, ldx, ldg, true);
     if (sc.status != DS_OK) return sc.status;
-    if (segments_overlap(segs, S)) return DS_ERR_BAD_SHAPE;
-    if (sc.n_tiles == 0) return DS_OK;
-    const size_t need = static_cast<size_t>(sc.n_tiles) * sizeof(Tile);
+    const int rc = check_disjoint(segs, S);
+    if (rc != DS_OK) return rc;
+    if (sc.n_entries == 0) return DS_OK;
+    const size_t need = static_cast<size_t>(sc.n_entries + 1) * sizeof(Tile);
     if (!plan || !ds::aligned16(plan) || plan_bytes < need) return DS_ERR_WORKSPACE;
 
-    std::vector<Tile> table;
-    table.reserve(static_cast<size_t>(sc.n_tiles));
-    for (int32_t s = 0; s < S; ++s) {
-        for (int64_t done = 0; done < segs[s].length; done += kPlanTileCols) {
-            const int64_t left = segs[s].length - done;
-            table.push_back(Tile{segs[s].offset + done,
-                                 static_cast<int32_t>(left < kPlanTileCols ? left : kPlanTileCols), 0});
-        }
-    }
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (hipMemcpyAsync(plan, table.data(), need, hipMemcpyHostToDevice, st) != hipSuccess) return DS_ERR_HIP;
-    // the host table dies with this call, so the copy must have finished
-    if (hipStreamSynchronize(st) != hipSuccess) return DS_ERR_HIP;
+    PlanBatch batch;
+    batch.header.id = sc.id;
+    batch.header.n_segments = S;
+    batch.header.n_entries = static_cast<int32_t>(sc.n_entries);
+    int64_t first_entry = 0;
+    for (int32_t s0 = 0; s0 < S; s0 += kPlanBatch) {
+        batch.count = S - s0 < kPlanBatch ? S - s0 : kPlanBatch;
+        batch.with_header = s0 == 0;
+        for (int32_t j = 0; j < kPlanBatch; ++j) {
+            const bool used = j < batch.count;
+            batch.offset[j] = used ? segs[s0 + j].offset : 0;
+            batch.length[j] = used ? segs[s0 + j].length : 0;
+            batch.first_entry[j] = first_entry;
+            if (used) first_entry += (segs[s0 + j].length + kPlanTileCols - 1) / kPlanTileCols;
+        }
+        const hipError_t err = ds::launch_kernel(plan_fill_kernel, dim3(static_cast<uint32_t>(batch.count)),
+                                                 dim3(kPlanThreads), 0, st, static_cast<Tile*>(plan), batch);
+        if (err != hipSuccess) return DS_ERR_HIP;
+    }
+    *plan_id_out = sc.id;
     return DS_OK;
 }
 
 extern "C" int ds_group_sync_ragged(void* X, const void* G, int32_t g_dtype, const ds_segment* segs,
                                     int32_t S, int64_t ldx, int64_t ldg, int32_t W, const int32_t* perm,
                                     const int32_t* off, int32_t n_groups, float lr, const void* plan,
-                                    size_t plan_bytes, void* stream) {
+                                    size_t plan_bytes, uint64_t plan_id, void* stream) {
     return group_sync_ragged(X, G, g_dtype, segs, S, ldx, ldg, W, perm, off, n_groups, lr, nullptr, plan, plan_bytes,
-                             stream);
+                             plan_id, stream);
 }
 
 extern "C" int ds_group_sync_ragged_opt(void* X, const void* G, int32_t g_dtype, const ds_segment* segs,
                                         int32_t S, int64_t ldx, int64_t ldg, int32_t W, const int32_t* perm,
                                         const int32_t* off, int32_t n_groups, float lr, const ds_local_opt* opt,
-                                        const void* plan, size_t plan_bytes, void* stream) {
+                                        const void* plan, size_t plan_bytes, uint64_t plan_id, void* stream) {
     return group_sync_ragged(X, G, g_dtype, segs, S, ldx, ldg, W, perm, off, n_groups, lr, opt, plan, plan_bytes,
-                             stream);
+                             plan_id, stream);
 }

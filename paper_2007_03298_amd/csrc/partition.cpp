@@ -17,6 +17,7 @@ extern "C" const char* ds_status_string(int status) {
         case DS_ERR_WORKSPACE: return "DS_ERR_WORKSPACE: workspace or plan buffer missing, misaligned or too small";
         case DS_ERR_HIP: return "DS_ERR_HIP: HIP call or kernel launch failed";
         case DS_ERR_TOPOLOGY: return "DS_ERR_TOPOLOGY: rack table is not a usable topology";
+        case DS_ERR_HOST_MEMORY: return "DS_ERR_HOST_MEMORY: host allocation failed";
         default: return "unknown ds_status";
     }
 }
@@ -86,18 +87,16 @@ extern "C" int ds_partition(uint64_t seed, uint64_t t, int32_t W, const int32_t*
 }
 
 int ds::pack_partition(int32_t W, const int32_t* perm, const int32_t* off, int32_t n_groups,
-                       PartitionArg* out, int32_t* max_size, int32_t* equal_size) {
+                       PartitionArg* out, int32_t* max_size) {
     if (!perm || !off) return DS_ERR_NULL;
     if (W < 1 || W > DS_MAX_W) return DS_ERR_BAD_W;
     if (n_groups < 1 || n_groups > W) return DS_ERR_BAD_SIZES;
     if (off[0] != 0 || off[n_groups] != W) return DS_ERR_BAD_PART;
     int32_t largest = 0;
-    bool all_equal = true;
     for (int32_t k = 0; k < n_groups; ++k) {
         const int64_t sz = static_cast<int64_t>(off[k + 1]) - off[k];
         if (sz < 1 || sz > W) return DS_ERR_BAD_PART;
         if (sz > largest) largest = static_cast<int32_t>(sz);
-        if (sz != static_cast<int64_t>(off[1]) - off[0]) all_equal = false;
     }
     bool seen[DS_MAX_W] = {};
     for (int32_t q = 0; q < W; ++q) {
@@ -113,6 +112,5 @@ int ds::pack_partition(int32_t W, const int32_t* perm, const int32_t* off, int32
         out->off[k >> 2] |= edge << ((k & 3) * 8);
     }
     *max_size = largest;
-    *equal_size = all_equal ? largest : 0;
     return DS_OK;
 }

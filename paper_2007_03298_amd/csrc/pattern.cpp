@@ -3,6 +3,7 @@
 // Host-only integer code: the division of iteration t is computed directly
 // from t (nothing is carried between iterations), so it can stand in for
 // ds_partition wherever the rack of every worker is known.
+#include <cmath>
 #include <numeric>
 
 #include "ds_internal.h"
@@ -147,5 +148,122 @@ extern "C" int ds_pattern_period(int32_t W, const int32_t* rack_of, const uint8_
     }
     if (has_links && n_regular > 0 && n_regular < n_racks) fold(n_regular);   // partner of the delayed racks
     *period_out = period;
+    return DS_OK;
+}
+
+// ---------------------------------------------------------------- premise of the consensus bound
+
+namespace {
+
+constexpr int kN = DS_MAX_W;
+typedef double Matrix[kN][kN];   // the leading n x n block is used
+
+double frobenius(const Matrix& a, int n) {
+    double s = 0.0;
+    for (int i = 0; i < n; ++i)
+        for (int j = 0; j < n; ++j) s += a[i][j] * a[i][j];
+    return std::sqrt(s);
+}
+
+// Spectral radius of a (destroyed) by Gelfand's formula along the powers 2^j:
+// with a_0 = a and a_{j+1} = (a_j / ||a_j||)^2,  log rho = sum_j log||a_j|| / 2^j.
+// Every factor is normalised before it is squared, so nothing over- or
+// underflows, and after 64 squarings the neglected tail weighs 2^-64.
+double spectral_radius(Matrix& a, Matrix& tmp, int n) {
+    double log_rho = 0.0, weight = 1.0;
+    for (int iter = 0; iter < 64; ++iter) {
+        const double norm = frobenius(a, n);
+        if (!(norm > 0.0)) return 0.0;   // nilpotent: every eigenvalue is 0
+        log_rho += weight * std::log(norm);
+        weight *= 0.5;
+        for (int i = 0; i < n; ++i)
+            for (int j = 0; j < n; ++j) tmp[i][j] = a[i][j] / norm;
+        for (int i = 0; i < n; ++i) {
+            for (int j = 0; j < n; ++j) {
+                double s = 0.0;
+                for (int k = 0; k < n; ++k) s += tmp[i][k] * tmp[k][j];
+                a[i][j] = s;
+            }
+        }
+    }
+    return std::exp(log_rho);
+}
+
+int find_root(int32_t* parent, int v) {
+    while (parent[v] != v) {
+        parent[v] = parent[parent[v]];
+        v = parent[v];
+    }
+    return v;
+}
+
+}  // namespace
+
+extern "C" int ds_pattern_check(int32_t W, int32_t B, const int32_t* perms, const int32_t* offs,
+                                const int32_t* n_groups, int32_t* connected_out, double* rho_out,
+                                double* sigma_out) {
+    if (!perms || !offs || !n_groups || !connected_out) return DS_ERR_NULL;
+    if (W < 1 || W > DS_MAX_W) return DS_ERR_BAD_W;
+    if (B < 1) return DS_ERR_BAD_SHAPE;
+    ds::PartitionArg unused;
+    int32_t largest = 0;
+    for (int32_t k = 0; k < B; ++k) {
+        const int rc = ds::pack_partition(W, perms + static_cast<int64_t>(k) * W, offs + static_cast<int64_t>(k) * (W + 1),
+                                          n_groups[k], &unused, &largest);
+        if (rc != DS_OK) return rc;
+    }
+
+    // connectivity of the union of the groups over the period
+    int32_t parent[DS_MAX_W];
+    for (int32_t w = 0; w < W; ++w) parent[w] = w;
+    for (int32_t k = 0; k < B; ++k) {
+        const int32_t* perm = perms + static_cast<int64_t>(k) * W;
+        const int32_t* off = offs + static_cast<int64_t>(k) * (W + 1);
+        for (int32_t g = 0; g < n_groups[k]; ++g)
+            for (int32_t q = off[g] + 1; q < off[g + 1]; ++q)
+                parent[find_root(parent, perm[q])] = find_root(parent, perm[off[g]]);
+    }
+    int32_t components = 0;
+    for (int32_t w = 0; w < W; ++w) components += find_root(parent, w) == w;
+    *connected_out = components == 1;
+    if (!rho_out && !sigma_out) return DS_OK;
+
+    // M = W_{B-1} ... W_0: applying W_k on the left replaces the rows of a group by their mean
+    Matrix m, a, tmp;   // 3 x 32 KiB on the stack
+    for (int i = 0; i < W; ++i)
+        for (int j = 0; j < W; ++j) m[i][j] = i == j ? 1.0 : 0.0;
+    for (int32_t k = 0; k < B; ++k) {
+        const int32_t* perm = perms + static_cast<int64_t>(k) * W;
+        const int32_t* off = offs + static_cast<int64_t>(k) * (W + 1);
+        for (int32_t g = 0; g < n_groups[k]; ++g) {
+            const int32_t n = off[g + 1] - off[g];
+            if (n == 1) continue;
+            for (int j = 0; j < W; ++j) {
+                double s = 0.0;
+                for (int32_t q = off[g]; q < off[g + 1]; ++q) s += m[perm[q]][j];
+                s /= static_cast<double>(n);
+                for (int32_t q = off[g]; q < off[g + 1]; ++q) m[perm[q]][j] = s;
+            }
+        }
+    }
+    // the part of M that acts on what is orthogonal to consensus
+    const double mean = 1.0 / static_cast<double>(W);
+    for (int i = 0; i < W; ++i)
+        for (int j = 0; j < W; ++j) m[i][j] -= mean;
+    if (rho_out) {
+        for (int i = 0; i < W; ++i)
+            for (int j = 0; j < W; ++j) a[i][j] = m[i][j];
+        *rho_out = spectral_radius(a, tmp, W);
+    }
+    if (sigma_out) {
+        for (int i = 0; i < W; ++i) {
+            for (int j = 0; j < W; ++j) {
+                double s = 0.0;
+                for (int k = 0; k < W; ++k) s += m[k][i] * m[k][j];
+                a[i][j] = s;
+            }
+        }
+        *sigma_out = std::sqrt(spectral_radius(a, tmp, W));
+    }
     return DS_OK;
 }

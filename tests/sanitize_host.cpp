@@ -48,8 +48,8 @@ int main() {
                               off.data());
         if (rc != DS_OK) { std::printf("ds_partition failed: %d\n", rc); return 1; }
         ds::PartitionArg packed;
-        int32_t largest = 0, equal = 0;
-        rc = ds::pack_partition(W, perm.data(), off.data(), static_cast<int32_t>(sizes.size()), &packed, &largest, &equal);
+        int32_t largest = 0;
+        rc = ds::pack_partition(W, perm.data(), off.data(), static_cast<int32_t>(sizes.size()), &packed, &largest);
         if (rc != DS_OK) { std::printf("pack_partition rejected a valid division: %d\n", rc); return 1; }
         // unpack and compare
         for (int q = 0; q < W; ++q) {
@@ -59,7 +59,7 @@ int main() {
         // damaged divisions must be rejected, never read out of bounds
         std::vector<int32_t> bad = perm;
         bad[static_cast<size_t>(below(W))] = below(3) == 0 ? -1 - below(5) : W + below(100);
-        if (ds::pack_partition(W, bad.data(), off.data(), static_cast<int32_t>(sizes.size()), &packed, &largest, &equal) != DS_ERR_BAD_PART) {
+        if (ds::pack_partition(W, bad.data(), off.data(), static_cast<int32_t>(sizes.size()), &packed, &largest) != DS_ERR_BAD_PART) {
             std::printf("out-of-range worker accepted\n");
             return 1;
         }
@@ -85,12 +85,39 @@ int main() {
         const uint64_t t = next_u64();
         rc = ds_pattern(W, rack_of.data(), slow_rack.data(), R, slow_worker.data(), t, pperm.data(), poff.data(), &n_groups);
         if (rc != DS_OK) { std::printf("ds_pattern failed: %d\n", rc); return 1; }
-        rc = ds::pack_partition(W, pperm.data(), poff.data(), n_groups, &packed, &largest, &equal);
+        rc = ds::pack_partition(W, pperm.data(), poff.data(), n_groups, &packed, &largest);
         if (rc != DS_OK) { std::printf("pattern is not a valid division: %d\n", rc); return 1; }
         std::vector<int32_t> again(static_cast<size_t>(W)), again_off(static_cast<size_t>(W) + 1);
         int32_t n_again = 0;
         rc = ds_pattern(W, rack_of.data(), slow_rack.data(), R, slow_worker.data(), t + period, again.data(), again_off.data(), &n_again);
         if (rc != DS_OK || n_again != n_groups || again != pperm) { std::printf("pattern is not periodic\n"); return 1; }
+        // premise of the consensus bound on one period of the pattern (capped) and on a damaged list;
+        // every 50th round only: the fp64 matrix powers are slow under the sanitizers
+        if (iter % 50 == 0) {
+            const int Bp = static_cast<int>(period < 24 ? period : 24);
+            std::vector<int32_t> perms(static_cast<size_t>(Bp) * W), offs(static_cast<size_t>(Bp) * (W + 1)), counts(static_cast<size_t>(Bp));
+            for (int k = 0; k < Bp; ++k) {
+                rc = ds_pattern(W, rack_of.data(), slow_rack.data(), R, slow_worker.data(), t + static_cast<uint64_t>(k),
+                                perms.data() + static_cast<size_t>(k) * W, offs.data() + static_cast<size_t>(k) * (W + 1),
+                                &counts[static_cast<size_t>(k)]);
+                if (rc != DS_OK) { std::printf("ds_pattern failed inside a period: %d\n", rc); return 1; }
+            }
+            int32_t connected = -1;
+            double rho = -1.0, sigma = -1.0;
+            rc = ds_pattern_check(W, Bp, perms.data(), offs.data(), counts.data(), &connected, &rho, &sigma);
+            if (rc != DS_OK || connected < 0 || !(rho >= 0.0 && rho <= 1.0 + 1e-9) || !(sigma >= rho - 1e-9 && sigma <= 1.0 + 1e-9) ||
+                (connected == 1) != (sigma < 1.0 - 1e-9)) {
+                std::printf("ds_pattern_check: rc %d connected %d rho %g sigma %g\n", rc, connected, rho, sigma);
+                return 1;
+            }
+            // (a full period need not be connected: a rack whose only worker without NIC contention is
+            //  always its representative never mixes its other workers with anybody else)
+            perms[static_cast<size_t>(below(Bp * W))] = W + below(50);
+            if (ds_pattern_check(W, Bp, perms.data(), offs.data(), counts.data(), &connected, &rho, &sigma) != DS_ERR_BAD_PART) {
+                std::printf("ds_pattern_check accepted a damaged list\n");
+                return 1;
+            }
+        }
         rack_of[static_cast<size_t>(below(W))] = R + below(4);   // rack index out of range
         if (ds_pattern(W, rack_of.data(), slow_rack.data(), R, slow_worker.data(), t, pperm.data(), poff.data(), &n_groups) != DS_ERR_TOPOLOGY) {
             std::printf("bad rack index accepted\n");

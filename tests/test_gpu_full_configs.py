@@ -143,7 +143,7 @@ def test_config5_ragged_full_size():
 
     nbytes = ds.ds_ragged_plan_bytes(segs)
     plan = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
-    ds.ds_ragged_plan(segs, ld, ld, plan, nbytes)
+    plan_id = ds.ds_ragged_plan(segs, ld, ld, plan, nbytes)
     packed = ds.pack_segments(segs)
     G = torch.empty(W, ld, dtype=torch.bfloat16, device=DEV)
     worst_step = worst_traj = 0.0
@@ -154,7 +154,7 @@ def test_config5_ragged_full_size():
         assert perm.tolist() == po.tolist() and off.tolist() == oo.tolist()
         before = X.index_select(1, cols_t).cpu().numpy()
         Gw = wl.tensor_to_numpy(G.index_select(1, cols_t))
-        ds.ds_group_sync_ragged(X, G, ds.DS_BF16, packed, ld, ld, W, perm, off, cfg.lr, plan, nbytes)
+        ds.ds_group_sync_ragged(X, G, ds.DS_BF16, packed, ld, ld, W, perm, off, cfg.lr, plan, nbytes, plan_id)
         torch.cuda.synchronize()
         got = X.index_select(1, cols_t).cpu().numpy()
         # the oracle steps only the sampled columns that lie inside a segment

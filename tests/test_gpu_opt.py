@@ -83,13 +83,13 @@ def test_extended_step_ragged_bf16():
     Gh = wl.tensor_to_numpy(G)
     nbytes = ds.ds_ragged_plan_bytes(segs)
     plan = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
-    ds.ds_ragged_plan(segs, ld, ld, plan, nbytes)
+    plan_id = ds.ds_ragged_plan(segs, ld, ld, plan, nbytes)
     opt = ds.local_opt(V, ld, 0.9, 1e-3, S, ld, 0.5)
     for t in range(3):
         perm, off = ds.ds_partition(2, t, W, sizes)
         Xo, Vo, So = wl.tensor_to_numpy(X), wl.tensor_to_numpy(V), wl.tensor_to_numpy(S)
         before = (Xo.copy(), Vo.copy(), So.copy())
-        ds.ds_group_sync_ragged_opt(X, G, ds.DS_BF16, segs, ld, ld, W, perm, off, 0.01, opt, plan, nbytes)
+        ds.ds_group_sync_ragged_opt(X, G, ds.DS_BF16, segs, ld, ld, W, perm, off, 0.01, opt, plan, nbytes, plan_id)
         torch.cuda.synchronize()
         covered = np.zeros(ld, dtype=bool)
         for o, n in segs:

@@ -177,13 +177,13 @@ def check_ragged(W, sizes, segs, ld, bf16, seed):
     Gh = wl.tensor_to_numpy(G)
     nbytes = ds.ds_ragged_plan_bytes(segs)
     plan = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=DEV)
-    ds.ds_ragged_plan(segs, ld, ld, plan, nbytes)
+    plan_id = ds.ds_ragged_plan(segs, ld, ld, plan, nbytes)
     packed = ds.pack_segments(segs)
     for t in range(2):
         perm, off = ds.ds_partition(4, t, W, sizes)
         before = wl.tensor_to_numpy(X)
         ds.ds_group_sync_ragged(X, G, ds.DS_BF16 if bf16 else ds.DS_F32, packed, ld, ld, W, perm, off, 0.01,
-                                plan, nbytes)
+                                plan, nbytes, plan_id)
         torch.cuda.synchronize()
         got = wl.tensor_to_numpy(X)
         want = before.copy()
@@ -205,9 +205,9 @@ def test_ragged_matches_oracle_small(bf16):
             (20248, 511), (20760, 512), (21272, 513)]
     check_ragged(8, [4, 4], segs, 21788, bf16, 21)
     check_ragged(8, [2, 3, 3], segs[::-1], 21788, bf16, 22)          # any order of the list
-    check_ragged(8, [8], segs, 21788, bf16, 25)                      # one vector per lane
-    check_ragged(8, [2] * 4, segs, 21788, bf16, 26)                  # four vectors per lane
-    check_ragged(8, [1] * 8, segs, 21788, bf16, 27)                  # eight vectors per lane
+    check_ragged(8, [8], segs, 21788, bf16, 25)                      # a full round of eight members
+    check_ragged(8, [2] * 4, segs, 21788, bf16, 26)                  # pairs
+    check_ragged(8, [1] * 8, segs, 21788, bf16, 27)                  # groups of one
     check_ragged(32, [4] * 8, [(128 * i, 61 + i) for i in range(40)], 128 * 41, bf16, 23)
 
 
@@ -219,11 +219,54 @@ def test_ragged_equals_flat_on_one_segment():
     segs = [(0, P)]
     nbytes = ds.ds_ragged_plan_bytes(segs)
     plan = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
-    ds.ds_ragged_plan(segs, ld, ld, plan, nbytes)
-    ds.ds_group_sync_ragged(X, G, ds.DS_BF16, segs, ld, ld, W, perm, off, 0.01, plan, nbytes)
+    plan_id = ds.ds_ragged_plan(segs, ld, ld, plan, nbytes)
+    ds.ds_group_sync_ragged(X, G, ds.DS_BF16, segs, ld, ld, W, perm, off, 0.01, plan, nbytes, plan_id)
     ds.ds_group_sync(X2, G, ds.DS_BF16, P, ld, ld, W, perm, off, 0.01)
     torch.cuda.synchronize()
     assert torch.equal(X, X2)
+
+
+def test_ragged_launch_tells_a_plan_of_another_list():
+    W, ld = 8, 12288
+    X, G = random_stacks(27, W, ld, ld, True)
+    before = X.clone()
+    perm, off = ds.ds_partition(1, 1, W, [4, 4])
+    mine, other = [(0, 3000), (4096, 2000)], [(0, 2500), (4096, 1500)]       # same number of plan entries
+    nbytes = ds.ds_ragged_plan_bytes(mine)
+    assert nbytes == ds.ds_ragged_plan_bytes(other)
+    plan = torch.zeros(nbytes, dtype=torch.uint8, device=DEV)
+    blank = torch.zeros(nbytes, dtype=torch.uint8, device=DEV)
+    plan_id = ds.ds_ragged_plan(mine, ld, ld, plan, nbytes)
+    assert plan_id != 0 and plan_id == ds.ds_ragged_plan(mine, ld, ld, plan, nbytes)     # a function of the list
+    # the host refuses a plan whose identity is not that of the list it is launched with
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_group_sync_ragged(X, G, ds.DS_BF16, other, ld, ld, W, perm, off, 0.01, plan, nbytes, plan_id)
+    assert e.value.status == -8
+    # the device leaves the stacks alone when the buffer does not hold the plan it is told to expect
+    ds.ds_group_sync_ragged(X, G, ds.DS_BF16, mine, ld, ld, W, perm, off, 0.01, blank, nbytes, plan_id)
+    torch.cuda.synchronize()
+    assert torch.equal(X, before)
+    other_plan = torch.zeros(nbytes, dtype=torch.uint8, device=DEV)
+    other_id = ds.ds_ragged_plan(other, ld, ld, other_plan, nbytes)
+    assert other_id != plan_id
+    ds.ds_group_sync_ragged(X, G, ds.DS_BF16, mine, ld, ld, W, perm, off, 0.01, other_plan, nbytes, plan_id)
+    torch.cuda.synchronize()
+    assert torch.equal(X, before)
+    # and the matching triple runs
+    ds.ds_group_sync_ragged(X, G, ds.DS_BF16, mine, ld, ld, W, perm, off, 0.01, plan, nbytes, plan_id)
+    torch.cuda.synchronize()
+    want = wl.tensor_to_numpy(before)
+    for o, n in mine:
+        oracle.step(want, wl.tensor_to_numpy(G), perm, off, 0.01, o, n)
+    assert scaled_error(wl.tensor_to_numpy(X), want) <= TOL_F32
+
+
+def test_plan_of_many_segments_is_written_in_batches():
+    # more segments than one launch of the plan kernel carries in its arguments
+    W = 4
+    segs = [(64 * i, 1 + (37 * i) % 64) for i in range(250)]
+    ld = 64 * 250
+    check_ragged(W, [2, 2], segs, ld, False, 28)
 
 
 # ---------------------------------------------------------------- consensus
@@ -351,8 +394,8 @@ def test_layer_by_layer_launches_equal_the_ragged_launch():
     perm, off = ds.ds_partition(6, 0, W, sizes)
     nbytes = ds.ds_ragged_plan_bytes(segs)
     plan = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
-    ds.ds_ragged_plan(segs, ld, ld, plan, nbytes)
-    ds.ds_group_sync_ragged(X, G, ds.DS_BF16, segs, ld, ld, W, perm, off, 0.01, plan, nbytes)
+    plan_id = ds.ds_ragged_plan(segs, ld, ld, plan, nbytes)
+    ds.ds_group_sync_ragged(X, G, ds.DS_BF16, segs, ld, ld, W, perm, off, 0.01, plan, nbytes, plan_id)
     streams = [torch.cuda.Stream() for _ in range(3)]
     torch.cuda.synchronize()
     for k, (o, n) in enumerate(reversed(segs)):

@@ -139,13 +139,25 @@ def test_group_sync_argument_errors():
     assert sync_status(off=[1, 4, 8]) == -4
 
 
+def test_rows_longer_than_one_launch_covers_are_refused_before_any_device_call():
+    # gridDim.x * 64 threads must stay below 2^32: 2^26 - 1 tiles of 256 columns
+    assert ds.DS_MAX_COLUMNS == (2**26 - 1) * 256
+    too_long = ds.DS_MAX_COLUMNS + 4
+    assert sync_status(P=too_long, ldx=too_long, ldg=too_long, W=1, perm=[0], off=[0, 1]) == -5
+    assert sync_status(P=2**40, ldx=2**40, ldg=2**40) == -5
+    need = ds.ds_consensus_workspace_bytes(8, 100)
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_consensus(A, too_long, too_long, 8, B, 3 * B, need, stream=0)
+    assert e.value.status == -5
+
+
 def test_group_sync_empty_is_ok_without_a_device():
     ds.ds_group_sync(A, B, 0, 0, 16, 16, 8, PERM8, OFF8, 0.1, stream=0)   # P == 0: nothing enqueued
 
 
-def ragged_status(segs, X=A, G=B, ldx=4096, ldg=4096, plan=A, plan_bytes=1 << 20):
+def ragged_status(segs, X=A, G=B, ldx=4096, ldg=4096, plan=A, plan_bytes=1 << 20, plan_id=1):
     with pytest.raises(ds.DsError) as e:
-        ds.ds_group_sync_ragged(X, G, 1, segs, ldx, ldg, 8, PERM8, OFF8, 0.1, plan, plan_bytes, stream=0)
+        ds.ds_group_sync_ragged(X, G, 1, segs, ldx, ldg, 8, PERM8, OFF8, 0.1, plan, plan_bytes, plan_id, stream=0)
     return e.value.status
 
 
@@ -157,31 +169,43 @@ def test_ragged_argument_errors():
     assert ragged_status([(0, 16)], plan=0) == -8
     assert ragged_status([(0, 16)], plan_bytes=8) == -8
     assert ragged_status([(0, 16)], plan=A + 8) == -8
+    assert ragged_status([(0, 16)], plan_bytes=16) == -8       # room for the header only
+    # a plan that was not built from this list: its identity is not the list's, whatever it is
+    for wrong in (0, 1, 12345, 2**64 - 1):
+        assert ragged_status([(0, 16), (64, 100)], plan_id=wrong) == -8
+    # one launch covers at most DS_MAX_COLUMNS columns, of a ragged list too
+    huge = ds.DS_MAX_COLUMNS + 2048
+    assert ragged_status([(0, huge)], ldx=huge, ldg=huge) == -5
     # all-empty segment lists enqueue nothing and need no plan
-    ds.ds_group_sync_ragged(A, B, 1, [(0, 0), (64, 0)], 4096, 4096, 8, PERM8, OFF8, 0.1, 0, 0, stream=0)
-    ds.ds_group_sync_ragged(A, B, 1, [], 4096, 4096, 8, PERM8, OFF8, 0.1, 0, 0, stream=0)
+    ds.ds_group_sync_ragged(A, B, 1, [(0, 0), (64, 0)], 4096, 4096, 8, PERM8, OFF8, 0.1, 0, 0, 0, stream=0)
+    ds.ds_group_sync_ragged(A, B, 1, [], 4096, 4096, 8, PERM8, OFF8, 0.1, 0, 0, 0, stream=0)
 
 
 def test_ragged_plan_bytes_and_plan_errors():
     assert ds.ds_ragged_plan_bytes([]) == 0
     assert ds.ds_ragged_plan_bytes([(0, 0)]) == 0
     one = ds.ds_ragged_plan_bytes([(0, 1)])
-    assert one == 16
-    # one 16-byte entry per tile; the tile width is the library's business, but the
-    # count is additive over segments and grows with the length
+    assert one == 32                                 # a header entry and one tile entry, 16 bytes each
+    # the tile width is the library's business, but the entry count is additive
+    # over segments and grows with the length
     a, b, c = (0, 100000), (100096, 7), (200000, 12345)
-    assert ds.ds_ragged_plan_bytes([a, b, c]) == sum(ds.ds_ragged_plan_bytes([x]) for x in (a, b, c))
-    assert ds.ds_ragged_plan_bytes([b]) == 16
-    assert ds.ds_ragged_plan_bytes([a]) > ds.ds_ragged_plan_bytes([c]) > 16
+    entries = lambda segs: ds.ds_ragged_plan_bytes(segs) // 16 - 1
+    assert entries([a, b, c]) == sum(entries([x]) for x in (a, b, c))
+    assert entries([b]) == 1
+    assert entries([a]) > entries([c]) > 1
     assert ds.ds_ragged_plan_bytes([a]) % 16 == 0
     assert ds.ds_ragged_plan_bytes([(3, 5)]) == 0   # invalid list
     with pytest.raises(ds.DsError) as e:
         ds.ds_ragged_plan([(0, 64), (32, 64)], 4096, 4096, A, 1 << 20, stream=0)   # overlap
     assert e.value.status == -5
     with pytest.raises(ds.DsError) as e:
-        ds.ds_ragged_plan([(0, 64)], 4096, 4096, A, 8, stream=0)
+        ds.ds_ragged_plan([(0, 64)], 4096, 4096, A, 16, stream=0)
     assert e.value.status == -8
-    ds.ds_ragged_plan([(0, 0)], 4096, 4096, 0, 0, stream=0)   # nothing to build
+    assert ds.ds_ragged_plan([(0, 0)], 4096, 4096, 0, 0, stream=0) == 0   # nothing to build: identity 0
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    seg = binding.ds_segment(0, 64)
+    assert lib.ds_ragged_plan(ctypes.byref(seg), 1, ctypes.c_int64(64), ctypes.c_int64(64), ctypes.c_void_p(A),
+                              ctypes.c_size_t(64), None, None) == -1        # nowhere to put the identity
 
 
 def test_consensus_argument_errors():
@@ -238,6 +262,64 @@ def test_pattern_bit_exact_against_oracle_on_random_topologies():
             assert perm.tolist() == p2 and off.tolist() == o2
 
 
+def test_pattern_check_against_dense_mixing_matrices():
+    # Sec. IV-B2: connectivity of one period and the contraction factors of its product, against
+    # numpy on the dense matrices (eigenvalues of the product; 2-norm of its non-consensus part)
+    from oracle import mixing, pattern
+    r = np.random.default_rng(78)
+    seen_disconnected = 0
+    for trial in range(300):
+        if trial % 3 == 0:
+            # an arbitrary periodic list of random divisions (often not connected when short)
+            W = int(r.integers(1, 20))
+            divisions = []
+            for _ in range(int(r.integers(1, 4))):
+                cuts = sorted(set(r.integers(1, W, size=int(r.integers(0, W))).tolist())) if W > 1 else []
+                edges = [0] + cuts + [W]
+                divisions.append((r.permutation(W).tolist(), edges))
+        else:
+            rack_of, slow_rack, slow_worker = random_topology(r)
+            W = len(rack_of)
+            Bp = min(pattern.period(rack_of, slow_rack, slow_worker), 60)
+            divisions = [pattern.partition(rack_of, slow_rack, slow_worker, t) for t in range(Bp)]
+        connected, rho, sigma = ds.ds_pattern_check(W, divisions)
+        M = mixing.product([mixing.mixing_matrix(p, o) for p, o in divisions])
+        want_rho = mixing.second_eigenvalue(M) if W > 1 else 0.0
+        want_sigma = mixing.contraction_norm(M)
+        # components of the union graph, by brute force: boolean closure of the summed adjacency
+        reach = sum(mixing.mixing_matrix(p, o) for p, o in divisions) > 0
+        for _ in range(7):                       # paths of up to 2^7 >= DS_MAX_W edges
+            reach = (reach.astype(np.int64) @ reach.astype(np.int64)) > 0
+        want_connected = bool(reach.all())
+        assert connected == want_connected
+        assert abs(rho - want_rho) <= 1e-7 * max(1.0, want_rho) + 1e-9, (trial, rho, want_rho)
+        assert abs(sigma - want_sigma) <= 1e-9
+        assert (rho < 1 - 1e-9) == connected and (sigma < 1 - 1e-9) == connected
+        assert rho <= sigma + 1e-12
+        seen_disconnected += not connected
+    assert 10 < seen_disconnected < 290
+    # the testbed layouts of Sec. V-A5 are connected over a period; one iteration of them is not
+    static = ([0, 0, 0, 0, 1, 1, 1, 1], [0, 0], [0] * 8)
+    period = [tuple(a.tolist() for a in ds.ds_pattern(*static, t)) for t in range(ds.ds_pattern_period(*static))]
+    assert ds.ds_pattern_check(8, period)[0] and not ds.ds_pattern_check(8, period[:1])[0]
+    # a single group of everyone reaches consensus in one step
+    assert ds.ds_pattern_check(5, [(list(range(5)), [0, 5])]) == (True, 0.0, 0.0)
+
+
+def test_pattern_check_errors():
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    i32 = lambda v: (ctypes.c_int32 * len(v))(*v)
+    out = ctypes.c_int32(7)
+    call = lambda W, Bn, perm, off, n: lib.ds_pattern_check(W, Bn, i32(perm), i32(off), i32(n), ctypes.byref(out), None, None)
+    assert call(4, 1, [0, 1, 2, 3], [0, 2, 4, 0, 0], [2]) == 0 and out.value == 0
+    assert call(0, 1, [0], [0, 0], [1]) == -2
+    assert call(4, 0, [0, 1, 2, 3], [0, 2, 4, 0, 0], [2]) == -5
+    assert call(4, 1, [0, 1, 2, 2], [0, 2, 4, 0, 0], [2]) == -4
+    assert call(4, 1, [0, 1, 2, 3], [0, 2, 3, 0, 0], [2]) == -4
+    assert call(4, 1, [0, 1, 2, 3], [0, 2, 4, 0, 0], [0]) == -3
+    assert lib.ds_pattern_check(4, 1, None, i32([0, 4]), i32([1]), ctypes.byref(out), None, None) == -1
+
+
 def test_pattern_testbed_layouts():
     # the three worker layouts of the paper's testbed (Sec. V-A5)
     static = ([0, 0, 0, 0, 1, 1, 1, 1], [0, 0], [0] * 8)
@@ -282,7 +364,7 @@ def test_extended_step_argument_errors():
     ds.ds_group_sync_opt(A, B, 0, 0, 16, 16, 8, PERM8, OFF8, 0.1, ds.local_opt(V=2 * B, ldv=16), stream=0)
     with pytest.raises(ds.DsError) as e:
         ds.ds_group_sync_ragged_opt(A, B, 1, [(0, 64)], 4096, 4096, 8, PERM8, OFF8, 0.1,
-                                    ds.local_opt(V=2 * B, ldv=32), A, 1 << 20, stream=0)
+                                    ds.local_opt(V=2 * B, ldv=32), A, 1 << 20, 1, stream=0)
     assert e.value.status == -5                                      # buffer pitch ends before the segment
 
 
