@@ -347,6 +347,32 @@ int ds_consensus(const void* X, int64_t P, int64_t ld, int32_t W, double* dev_ou
                  size_t workspace_bytes, void* stream);
 
 /*
+ * ds_consensus_static -- ds_consensus without a workspace argument, for callers
+ * that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  The per-workgroup partial
+ * sums go to an array that is part of the library's device image (4 MiB:
+ * 8192 partial rows of DS_MAX_W fp64 sums, the largest workspace ds_consensus
+ * ever asks for), held by every GPU the library runs on until the process
+ * ends.  The call allocates and frees nothing and calls no routine that does.
+ * Same kernels and same result, bit for bit, as ds_consensus.
+ *
+ * Limits: the array covers every W <= DS_MAX_W and every P <= DS_MAX_COLUMNS
+ * (a workgroup walks as many column tiles as it takes to stay within 8192
+ * workgroups); anything larger is refused as in ds_consensus (DS_ERR_BAD_W,
+ * DS_ERR_BAD_SHAPE).  The first call on a device looks up the array's address
+ * there (hipGetSymbolAddress, with that device current) and keeps it; make that
+ * first call outside stream capture.  The array keeps the last call's partial
+ * sums; every launch overwrites all the entries it later reads, so nothing has
+ * to be cleared.  All calls on one GPU share the one array: two calls whose
+ * kernels may run at the same time (different streams, or graphs launched
+ * side by side) race and give wrong norms; order them on one stream or with
+ * events.
+ * Arguments and errors as ds_consensus without the workspace;
+ * DS_ERR_HIP also if the array's address cannot be obtained.
+ */
+int ds_consensus_static(const void* X, int64_t P, int64_t ld, int32_t W, double* dev_out, void* stream);
+
+/*
  * ds_consensus_grouped -- the same norms for a stack whose rows are known to be
  * identical inside every group of the given division, which is the state
  * right after ds_group_sync* with that division (Listing 1: members leave

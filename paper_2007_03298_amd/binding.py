@@ -24,7 +24,7 @@ DS_MAX_COLUMNS = ((1 << 26) - 1) * 256
 
 EXPORTS = ("ds_status_string", "ds_partition", "ds_pattern", "ds_pattern_period", "ds_pattern_check", "ds_group_sync",
            "ds_ragged_plan_bytes", "ds_ragged_plan", "ds_group_sync_ragged", "ds_group_sync_opt",
-           "ds_group_sync_ragged_opt", "ds_consensus_workspace_bytes", "ds_consensus", "ds_consensus_grouped",
+           "ds_group_sync_ragged_opt", "ds_consensus_workspace_bytes", "ds_consensus", "ds_consensus_static", "ds_consensus_grouped",
            "ds_padded_ld")
 
 
@@ -83,6 +83,8 @@ def _load() -> ctypes.CDLL:
     lib.ds_consensus_workspace_bytes.argtypes = [i32, i64]
     lib.ds_consensus.restype = ctypes.c_int
     lib.ds_consensus.argtypes = [vp, i64, i64, i32, vp, vp, sz, vp]
+    lib.ds_consensus_static.restype = ctypes.c_int
+    lib.ds_consensus_static.argtypes = [vp, i64, i64, i32, vp, vp]
     lib.ds_consensus_grouped.restype = ctypes.c_int
     lib.ds_consensus_grouped.argtypes = [vp, i64, i64, i32, i32p, i32p, i32, vp, vp, sz, vp]
     lib.ds_padded_ld.restype = i64
@@ -284,6 +286,10 @@ def ds_consensus_workspace_bytes(W: int, P: int) -> int:
 def ds_consensus(X, P: int, ld: int, W: int, dev_out, workspace, workspace_bytes: int, stream=None) -> None:
     _check(_lib.ds_consensus(_addr(X), P, ld, W, _addr(dev_out), _addr(workspace), workspace_bytes,
                              _stream(stream)), "ds_consensus")
+
+
+def ds_consensus_static(X, P: int, ld: int, W: int, dev_out, stream=None) -> None:
+    _check(_lib.ds_consensus_static(_addr(X), P, ld, W, _addr(dev_out), _stream(stream)), "ds_consensus_static")
 
 
 def ds_consensus_grouped(X, P: int, ld: int, W: int, perm, off, dev_out, workspace, workspace_bytes: int,

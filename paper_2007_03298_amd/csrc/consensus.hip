@@ -22,6 +22,8 @@
 //     square root.  No floating-point atomics: the result is deterministic.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+
 #include "ds_internal.h"
 #include "launch.h"
 
@@ -31,6 +33,13 @@ constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
 constexpr int kMaxBlocks = 8192;  // upper bound of the grid of the partial kernel
 constexpr int kFlushTiles = 32;   // tiles between two widenings of the fp32 lane accumulators
+
+// Partial rows of ds_consensus_static: the largest workspace ds_consensus ever
+// asks for (kMaxBlocks rows of DS_MAX_W sums, 4 MiB), resident on every GPU
+// the library runs on until the process ends.  In host code this name is only
+// a handle: the memory is reached through the address hipGetSymbolAddress
+// returns on each device.
+static __device__ __align__(256) double scratch[static_cast<size_t>(kMaxBlocks) * DS_MAX_W];
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
@@ -256,6 +265,44 @@ extern "C" int ds_consensus(const void* X, int64_t P, int64_t ld, int32_t W, dou
     for (int32_t i = 0; i < W; ++i) set_byte(tab.src, i, i);
     return launch_consensus<false>(static_cast<const float*>(X), P, ld, W, W, tab, dev_out,
                                    static_cast<double*>(workspace), static_cast<hipStream_t>(stream));
+}
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+// address of `scratch` on each device, resolved on the first call there
+std::atomic<double*> g_scratch_ptr[kMaxDevices];
+
+// The current device's copy of `scratch`, or NULL if its address cannot be had.
+double* scratch_on_current_device() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    double* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        // `dev` is current, so this is that device's copy of the array
+        if (hipGetSymbolAddress(reinterpret_cast<void**>(&ptr), HIP_SYMBOL(scratch)) != hipSuccess || !ptr)
+            return nullptr;
+        g_scratch_ptr[dev].store(ptr, std::memory_order_release);
+    }
+    return ptr;
+}
+
+}  // namespace
+
+extern "C" int ds_consensus_static(const void* X, int64_t P, int64_t ld, int32_t W, double* dev_out,
+                                   void* stream) {
+    // the workspace checks of ds_consensus are met by construction: any non-NULL aligned stand-in passes them
+    alignas(16) static const char stand_in = 0;
+    const int rc = check_consensus_args(X, P, ld, W, dev_out, &stand_in, ds_consensus_workspace_bytes(W, P));
+    if (rc != DS_OK) return rc;
+    static_assert(sizeof(scratch) >= static_cast<size_t>(kMaxBlocks) * 64 * sizeof(double),
+                  "the array holds the largest workspace ds_consensus asks for");
+    double* partial = scratch_on_current_device();
+    if (!partial) return DS_ERR_HIP;
+    RowTable tab = {};
+    for (int32_t i = 0; i < W; ++i) set_byte(tab.src, i, i);
+    return launch_consensus<false>(static_cast<const float*>(X), P, ld, W, W, tab, dev_out, partial,
+                                   static_cast<hipStream_t>(stream));
 }
 
 extern "C" int ds_consensus_grouped(const void* X, int64_t P, int64_t ld, int32_t W, const int32_t* perm,

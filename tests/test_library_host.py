@@ -232,6 +232,21 @@ def test_consensus_argument_errors():
     assert status(ws=3 * B + 8) == -8
 
 
+def test_static_scratch_consensus_checks_its_arguments_like_the_workspace_one():
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    lib.ds_consensus_static.restype = ctypes.c_int
+    lib.ds_consensus_static.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32,
+                                        ctypes.c_void_p, ctypes.c_void_p]
+    assert lib.ds_consensus_static(None, 16, 16, 8, B, None) == -1
+    assert lib.ds_consensus_static(A, 16, 16, 8, None, None) == -1
+    assert lib.ds_consensus_static(A, 16, 16, 65, B, None) == -2          # beyond its array: more than DS_MAX_W workers
+    assert lib.ds_consensus_static(A, 16, 16, 0, B, None) == -2
+    assert lib.ds_consensus_static(A, 17, 16, 8, B, None) == -5
+    assert lib.ds_consensus_static(A, ds.DS_MAX_COLUMNS + 4, 2**40, 8, B, None) == -5   # beyond one launch
+    assert lib.ds_consensus_static(A + 4, 16, 16, 8, B, None) == -6
+    assert lib.ds_consensus_static(A, 16, 16, 8, B + 4, None) == -6
+
+
 # ---- topology-aware pattern: library against the oracle's independent implementation ----
 
 def random_topology(r):
