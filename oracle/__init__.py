@@ -62,6 +62,9 @@ def _load():
         lib.orc_consensus.restype = ctypes.c_int
         lib.orc_consensus.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
                                       ctypes.c_int32, ctypes.c_void_p]
+        lib.orc_scaled_error.restype = ctypes.c_double
+        lib.orc_scaled_error.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
+                                         ctypes.c_int64, ctypes.c_int64, ctypes.c_int32]
         lib.orc_num_threads.restype = ctypes.c_int
         lib.orc_num_threads.argtypes = []
         _lib = lib
@@ -181,6 +184,23 @@ def consensus(X: np.ndarray, P: int | None = None) -> np.ndarray:
     if rc != 0:
         raise MemoryError("orc_consensus failed")
     return out
+
+
+def scaled_error(got: np.ndarray, want: np.ndarray, col0: int = 0, ncols: int | None = None) -> float:
+    """Yardstick of the parity tests: ``max |got - want| / max(|want|, rms(want row))`` over a
+    column window of two fp32 ``[W, ld]`` blocks (the rms over that window)."""
+    for A in (got, want):
+        if A.dtype != np.float32 or A.ndim != 2 or not A.flags.c_contiguous:
+            raise TypeError("fp32 C-contiguous [W, ld] arrays expected")
+    if got.shape[0] != want.shape[0]:
+        raise ValueError("row counts differ")
+    width = min(got.shape[1], want.shape[1])
+    if ncols is None:
+        ncols = width - col0
+    if col0 < 0 or ncols < 0 or col0 + ncols > width:
+        raise ValueError("column range outside the arrays")
+    return float(_load().orc_scaled_error(got.ctypes.data, want.ctypes.data, col0, ncols, got.shape[1],
+                                          want.shape[1], got.shape[0]))
 
 
 def num_threads() -> int:

@@ -254,3 +254,37 @@ int orc_consensus(const float *X, int64_t P, int64_t ld, int32_t W, double *d_ou
     free(xbar);
     return 0;
 }
+
+/* ------------------------------------------------------------------------- */
+/* Yardstick of the parity tests (not a step of the method): the largest      */
+/*     |got - want| / max(|want|, rms of want's row)                          */
+/* over columns col0 .. col0+ncols-1 of two fp32 [W, ld] blocks, the rms taken */
+/* over those same columns.  The denominator keeps "relative error" meaningful */
+/* for parameters near zero.  A NaN anywhere makes the result NaN.             */
+/* ------------------------------------------------------------------------- */
+double orc_scaled_error(const float *got, const float *want, int64_t col0, int64_t ncols,
+                        int64_t ld_got, int64_t ld_want, int32_t W)
+{
+    double worst = 0.0;
+    int bad = 0;
+    for (int32_t i = 0; i < W; ++i) {
+        const float *g = got + (int64_t)i * ld_got + col0;
+        const float *w = want + (int64_t)i * ld_want + col0;
+        double sq = 0.0;
+#pragma omp parallel for schedule(static) reduction(+ : sq)
+        for (int64_t p = 0; p < ncols; ++p) sq += (double)w[p] * (double)w[p];
+        double rms = ncols > 0 ? sqrt(sq / (double)ncols) : 0.0;
+        if (rms < 1e-30) rms = 1e-30;
+        double row_worst = 0.0;
+#pragma omp parallel for schedule(static) reduction(max : row_worst) reduction(| : bad)
+        for (int64_t p = 0; p < ncols; ++p) {
+            const double a = (double)g[p], b = (double)w[p];
+            const double den = fabs(b) > rms ? fabs(b) : rms;
+            const double e = fabs(a - b) / den;
+            if (e != e) bad |= 1;
+            if (e > row_worst) row_worst = e;
+        }
+        if (row_worst > worst) worst = row_worst;
+    }
+    return bad ? NAN : worst;
+}

@@ -116,12 +116,13 @@ def test_final_swa_average_is_one_group_of_all_workers():
 
 
 def test_config3_full_size_with_momentum_and_swa():
+    from test_gpu_full_configs import Stage, pieces_of
     cfg = wl.CONFIGS[3]
     W, P = cfg.W, cfg.P
     ld = wl.padded_ld(P)
     free, _ = torch.cuda.mem_get_info()
-    if free < 4 * W * ld * 4 + (2 << 30):
-        pytest.skip("needs four stacks of %.1f GB" % (W * ld * 4 / 1e9))
+    if free < 7 * W * ld * 4 + (3 << 30):
+        pytest.skip("needs seven stacks of %.1f GB" % (W * ld * 4 / 1e9))
     run = wl.Run(cfg, DEV, P=P, ld=ld)
     X = run.init_params()
     V = torch.zeros_like(X)
@@ -133,12 +134,31 @@ def test_config3_full_size_with_momentum_and_swa():
     cols_t = torch.from_numpy(cols).to(DEV)
     Xo, Vo, So = (A.index_select(1, cols_t).cpu().numpy() for A in (X, V, S))
     opt = ds.local_opt(V, ld, 0.9, 5e-4, S, ld, 0.9)
+    stage = Stage(W)
     for t in range(cfg.T):
         run.gradients(out=G)
         perm, off = ds.ds_partition(cfg.seed, t, W, cfg.sizes)
+        last = t == cfg.T - 1
+        if last:
+            Xb, Vb, Sb = X.clone(), V.clone(), S.clone()
         Gw = G.index_select(1, cols_t).cpu().numpy()
         ds.ds_group_sync_opt(X, G, ds.DS_F32, P, ld, ld, W, perm, off, cfg.lr, opt)
         torch.cuda.synchronize()
+        # trajectory on sampled windows: the oracle keeps its own X, V and S through all iterations
         oracle.step_opt(Xo, Gw, perm, off, cfg.lr, V=Vo, momentum=0.9, weight_decay=5e-4, S=So, factor=0.9)
         for A, want in ((X, Xo), (V, Vo), (S, So)):
             assert scaled_error(A.index_select(1, cols_t).cpu().numpy(), want) <= TOL_F32
+    # the last iteration on EVERY column: oracle from the GPU's own pre-step state, all three stacks compared
+    worst = 0.0
+    for c0, n in pieces_of(0, P):
+        xb, vb, sb = stage.pull("xb", Xb, c0, n), stage.pull("vb", Vb, c0, n), stage.pull("sb", Sb, c0, n)
+        g = stage.pull("g", G, c0, n)
+        xa, va, sa = stage.pull("xa", X, c0, n), stage.pull("va", V, c0, n), stage.pull("sa", S, c0, n)
+        torch.cuda.synchronize()
+        oracle.step_opt(xb, g, perm, off, cfg.lr, V=vb, momentum=0.9, weight_decay=5e-4, S=sb, factor=0.9)
+        for got, want in ((xa, xb), (va, vb), (sa, sb)):
+            err = oracle.scaled_error(got, want)
+            assert err == err
+            worst = max(worst, err)
+    print("  extended step, all columns of X, V, S: %.2e" % worst, flush=True)
+    assert worst <= TOL_F32

@@ -272,3 +272,30 @@ def test_lemma1_bound_on_the_rack_pattern():
         assert d.max() <= prev.max() + 1e-7                       # and it contracts
         prev = d
     assert prev.max() < 1e-2 * oracle.consensus(X0).max()
+
+
+def test_scaled_error_yardstick_against_its_definition():
+    # the parity yardstick is |a-b| / max(|b|, rms(b row)): numpy statement, hand values, window, NaN
+    r = np.random.default_rng(9)
+    want = r.normal(0, 0.02, (5, 1000)).astype(np.float32)
+    got = (want.astype(np.float64) * (1 + r.normal(0, 1e-6, want.shape))).astype(np.float32)
+    w64, g64 = want.astype(np.float64), got.astype(np.float64)
+    den = np.maximum(np.abs(w64), np.sqrt((w64**2).mean(axis=1, keepdims=True)))
+    np.testing.assert_allclose(oracle.scaled_error(got, want), (np.abs(g64 - w64) / den).max(), rtol=1e-12)
+    assert oracle.scaled_error(want, want) == 0.0
+    # one element off by 3 in a row of rms sqrt((3*1 + 25)/4): the rms is the denominator for a small element ...
+    b = np.array([[1, 1, 1, 5]], dtype=np.float32)
+    a = b.copy()
+    a[0, 0] += 3
+    assert abs(oracle.scaled_error(a, b) - 3 / np.sqrt(7.0)) < 1e-12
+    # ... and the element itself for a large one
+    a = b.copy()
+    a[0, 3] += 1
+    assert abs(oracle.scaled_error(a, b) - 1 / 5) < 1e-12
+    # a window looks at its own columns only, for the error and for the rms
+    a = b.copy()
+    a[0, 3] += 1
+    assert oracle.scaled_error(a, b, 0, 3) == 0.0
+    assert abs(oracle.scaled_error(a, b, 2, 2) - 1 / 5) < 1e-12
+    a[0, 1] = np.nan
+    assert np.isnan(oracle.scaled_error(a, b))
