@@ -4,22 +4,26 @@
 A step is one pass of the whole path over one batch of synthetic input, all
 resident in HBM before the clock starts:
     ds_partition (host)  ->  ds_group_sync (GPU)  ->  ds_consensus (GPU)
-The workload is configuration 3 of the benchmark set: W = 32 workers in groups
-of 8, P = 25,557,032 fp32 parameters per replica (ResNet-50-sized), gradients
-g_i = c_i (mu + 0.5 z_i), seed 2, lr 0.01, a new division every step.
+The headline workload is configuration 3 of the benchmark set: W = 32 workers
+in groups of 8, P = 25,557,032 fp32 parameters per replica (ResNet-50-sized),
+gradients g_i = c_i (mu + 0.5 z_i), seed 2, lr 0.01, a new division every step.
 
 Prints ONE JSON line.  ``value`` is the algorithmic bytes of a step
 (16 B per worker-element: read x, read g, write x, read x again for the
 consensus pass) divided by the wall-clock step time.  ``roofline`` is for the
 dominant kernel, the fused group-sync (12 B per worker-element), timed with
-events on the stream it is launched on.  ``cpu_baseline`` is the CPU oracle on
-the host cores, a reported figure only.
+events on the stream it is launched on.  ``all_configs`` holds a shorter run of
+each of the five benchmark configurations (kernel times as mean, median and
+minimum over the timed steps).  ``cpu_baseline`` is the CPU oracle on the host
+cores, a reported figure only.
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -29,6 +33,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published
 PROBE_SRC = os.path.join(ROOT, "bench_probe.hip")
 PROBE_LIB = os.path.join(ROOT, "libbench_probe.so")
+KERNEL_SRC = os.path.join(ROOT, "paper_2007_03298_amd", "csrc", "group_sync.hip")
 
 
 def build_probe() -> str:
@@ -53,53 +58,219 @@ def load_probe():
     return probe_copy
 
 
+def git_blob_id(path: str) -> str:
+    """What `git hash-object` prints for the file: identifies the kernel source a record belongs to."""
+    with open(path, "rb") as fh:
+        data = fh.read()
+    return hashlib.sha1(b"blob %d\0" % len(data) + data).hexdigest()
+
+
 def measured_traffic(name: str, workload: str):
     """HBM bytes per launch of the dominant kernel, from the rocprofv3 counter
     runs recorded under profiles/ (FETCH_SIZE and WRITE_SIZE, each scaled by
     what the same counter reads for the plain copy kernel).  The counters
-    cannot be read from inside this process, so the figure is the recorded one
-    and is reported only for the workload and layout it was measured on."""
+    cannot be read from inside this process, so the figure is the recorded one;
+    it is reported only for the workload and layout it was measured on and only
+    while the kernel source is the one it was measured with (null otherwise)."""
     path = os.path.join(ROOT, "profiles", name)
     try:
         with open(path) as fh:
             rec = json.load(fh)
-        return rec.get("hbm_bytes_per_launch") if rec.get("workload") == workload else None
+        if rec.get("workload") != workload or rec.get("kernel_source_blob") != git_blob_id(KERNEL_SRC):
+            return None
+        return rec.get("hbm_bytes_per_launch")
     except (OSError, ValueError):
         return None
 
 
-def cpu_baseline(cfg, X, G, budget_s: float = 10.0, max_iters: int = 200):
+def host_info():
+    model, mem_kib = "unknown", 0
+    try:
+        with open("/proc/cpuinfo") as fh:
+            for line in fh:
+                if line.startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+        with open("/proc/meminfo") as fh:
+            for line in fh:
+                if line.startswith("MemTotal"):
+                    mem_kib = int(line.split()[1])
+                    break
+    except OSError:
+        pass
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except AttributeError:
+        usable = os.cpu_count() or 1
+    return {"nproc": usable, "cpu_model": model, "ram_GiB": round(mem_kib / 2**20, 1)}
+
+
+def cpu_baseline(cfg, Xh, Gh, budget_s: float = 10.0, max_iters: int = 200):
     """The oracle, as it stands, on the host cores: whole configuration-3 stacks,
-    as many iterations as fit in about ``budget_s`` seconds of wall clock."""
-    import numpy as np
+    as many iterations as fit in about ``budget_s`` seconds of wall clock with all
+    of its threads, then a short leg on one thread."""
     import oracle
-    W, P = cfg.W, cfg.P
-    Xh = np.ascontiguousarray(X[:, :P].cpu().numpy())
-    Gh = np.ascontiguousarray(G[:, :P].cpu().numpy())
-    t_step = t_cons = 0.0
-    iters = 0
-    while iters < max_iters and (iters < 4 or t_step + t_cons < budget_s):
-        a = time.perf_counter()
-        perm, off = oracle.partition(cfg.seed, 1000 + iters, W, cfg.sizes)
-        oracle.step(Xh, Gh, perm, off, cfg.lr)
-        b = time.perf_counter()
-        oracle.consensus(Xh)
-        c = time.perf_counter()
-        t_step += b - a
-        t_cons += c - b
-        iters += 1
+    W, P = Xh.shape
+
+    def leg(limit_s, min_iters, t_base):
+        t_step = t_cons = 0.0
+        iters = 0
+        while iters < max_iters and (iters < min_iters or t_step + t_cons < limit_s):
+            a = time.perf_counter()
+            perm, off = oracle.partition(cfg.seed, t_base + iters, W, cfg.sizes)
+            oracle.step(Xh, Gh, perm, off, cfg.lr)
+            b = time.perf_counter()
+            oracle.consensus(Xh)
+            c = time.perf_counter()
+            t_step += b - a
+            t_cons += c - b
+            iters += 1
+        return iters, t_step, t_cons
+
+    threads = oracle.num_threads()
+    iters, t_step, t_cons = leg(budget_s, 4, 1000)
     total = t_step + t_cons
-    return {
+    oracle.set_num_threads(1)
+    try:
+        iters1, t_step1, t_cons1 = leg(4.0, 1, 2000)
+    finally:
+        oracle.set_num_threads(threads)
+    total1 = t_step1 + t_cons1
+    out = {
         "value": round(16.0 * W * P * iters / total / 1e9, 3),
         "unit": "GB/s",
-        "cores": oracle.num_threads(),
+        "cores": threads,
         "kind": "oracle",
         "sample": "all %d columns x %d workers of the same workload, %d iterations "
                   "(partition + step + consensus), %.1f s wall" % (P, W, iters, total),
         "ms_per_step": round(total / iters * 1e3, 2),
         "group_sync_ms": round(t_step / iters * 1e3, 2),
         "consensus_ms": round(t_cons / iters * 1e3, 2),
+        "single_thread": {"value": round(16.0 * W * P * iters1 / total1 / 1e9, 3), "unit": "GB/s", "cores": 1,
+                          "sample": "the same stacks, %d iteration(s), %.1f s wall" % (iters1, total1),
+                          "ms_per_step": round(total1 / iters1 * 1e3, 1),
+                          "group_sync_ms": round(t_step1 / iters1 * 1e3, 1),
+                          "consensus_ms": round(t_cons1 / iters1 * 1e3, 1)},
     }
+    out.update(host_info())
+    return out
+
+
+def spread(ms):
+    """Mean, median and minimum of a list of per-step milliseconds."""
+    return {"ms": round(statistics.fmean(ms), 4), "ms_median": round(statistics.median(ms), 4),
+            "ms_min": round(min(ms), 4)}
+
+
+class Workload:
+    """Stacks, division stream and launch closures of one benchmark configuration."""
+
+    def __init__(self, idx, dev, args):
+        import torch
+        import paper_2007_03298_amd as ds
+        from paper_2007_03298_amd import workloads as wl
+        self.torch, self.ds, self.idx = torch, ds, idx
+        cfg = self.cfg = wl.CONFIGS[idx]
+        self.W = W = cfg.W
+        if cfg.ragged:
+            # layer list of configuration 5: only the columns inside the segments are work
+            self.segs, self.ld, _ = wl.ragged_segments(cfg.seed)
+            self.P = sum(n for _, n in self.segs)
+            self.plan_bytes = ds.ds_ragged_plan_bytes(self.segs)
+            self.plan = torch.empty(self.plan_bytes, dtype=torch.uint8, device=dev)
+            self.packed = ds.pack_segments(self.segs)
+            self.plan_id = ds.ds_ragged_plan(self.packed, self.ld, self.ld, self.plan, self.plan_bytes)
+        else:
+            self.segs = None
+            self.P = cfg.P
+            self.ld = self.P if args.dense_rows else wl.padded_ld(self.P)   # rows on 1-KiB boundaries
+        self.g_bytes = 2 if cfg.bf16_grads else 4
+        self.g_dtype = ds.DS_BF16 if cfg.bf16_grads else ds.DS_F32
+        run = wl.Run(cfg, dev, P=self.ld, ld=self.ld)
+        self.X = run.init_params()
+        self.use_v = args.local_opt in ("momentum", "both")
+        self.use_s = args.local_opt in ("swa", "both")
+        self.V = torch.zeros_like(self.X) if self.use_v else None
+        self.S = self.X.clone() if self.use_s else None
+        self.weight_decay = 5e-4 if self.use_v else 0.0
+        self.opt = (ds.local_opt(self.V, self.ld, 0.9, self.weight_decay, self.S, self.ld, 0.9)
+                    if (self.use_v or self.use_s) else None)
+        self.Gs = [run.gradients() for _ in range(2)]      # gradient stacks resident in HBM, used in turn
+        self.P_cons = self.ld if cfg.ragged else self.P    # ragged: the norm runs over the whole arena
+        self.ws_bytes = ds.ds_consensus_workspace_bytes(W, self.P_cons)
+        self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=dev)
+        self.dev_out = torch.zeros(W, dtype=torch.float64, device=dev)
+        self.stream = torch.cuda.current_stream()
+        self.layerwise = None
+        self.sync_bytes = (8.0 + self.g_bytes + 8.0 * self.use_v + 8.0 * self.use_s) * W * self.P
+        self.cons_bytes = 4.0 * W * self.P_cons
+
+    def use_layerwise(self, n_streams):
+        self.layerwise = self.ds.LayerwiseSync(self.segs, n_streams) if n_streams > 0 else None
+
+    def step(self, t, ev=None):
+        ds, cfg, st = self.ds, self.cfg, self.stream
+        perm, off = ds.ds_partition(cfg.seed, t, self.W, cfg.sizes)
+        G = self.Gs[t % len(self.Gs)]
+        if ev:
+            ev[0].record(st)
+        if self.layerwise is not None:
+            # Sec. V-A1: one launch per layer, last layer first, on side streams; here all layers are
+            # ready at once and the main stream waits for all of them
+            self.layerwise.backward(self.X, G, self.g_dtype, self.ld, self.ld, self.W, perm, off, cfg.lr,
+                                    V=self.V, ldv=self.ld, momentum=0.9 if self.use_v else 0.0,
+                                    weight_decay=self.weight_decay, S=self.S, lds=self.ld, swa_factor=0.9, stream=st)
+            self.layerwise.wait_all(st)
+        elif cfg.ragged:
+            ds.ds_group_sync_ragged_opt(self.X, G, self.g_dtype, self.packed, self.ld, self.ld, self.W, perm, off,
+                                        cfg.lr, self.opt, self.plan, self.plan_bytes, self.plan_id, st)
+        else:
+            ds.ds_group_sync_opt(self.X, G, self.g_dtype, self.P, self.ld, self.ld, self.W, perm, off, cfg.lr,
+                                 self.opt, st)
+        if ev:
+            ev[1].record(st)
+        ds.ds_consensus(self.X, self.P_cons, self.ld, self.W, self.dev_out, self.ws, self.ws_bytes, st)
+        if ev:
+            ev[2].record(st)
+
+    def timed(self, warmup, steps, t0=0):
+        """`warmup` untimed steps, then `steps` timed ones: wall clock per step and per-kernel event times."""
+        torch = self.torch
+        for t in range(warmup):
+            self.step(t0 + t)
+        events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+        torch.cuda.synchronize()
+        a = time.perf_counter()
+        for k in range(steps):
+            self.step(t0 + warmup + k, events[k])
+        torch.cuda.synchronize()
+        b = time.perf_counter()
+        sync_ms = [e[0].elapsed_time(e[1]) for e in events]
+        cons_ms = [e[1].elapsed_time(e[2]) for e in events]
+        return (b - a) / steps * 1e3, sync_ms, cons_ms
+
+    def record(self, ms_step, sync_ms, cons_ms):
+        """Figures of one configuration for `all_configs`."""
+        sync, cons = spread(sync_ms), spread(cons_ms)
+        sync_gbps = self.sync_bytes / (sync["ms"] * 1e-3) / 1e9
+        cons_gbps = self.cons_bytes / (cons["ms"] * 1e-3) / 1e9
+        sync.update(GBps=round(sync_gbps, 1), frac=round(sync_gbps / HBM_PEAK_GBPS, 4),
+                    bytes_per_launch=int(self.sync_bytes))
+        cons.update(GBps=round(cons_gbps, 1), frac=round(cons_gbps / HBM_PEAK_GBPS, 4),
+                    bytes_per_launch=int(self.cons_bytes))
+        rec = {"workload": self.cfg.name, "W": self.W, "group_size": self.cfg.group, "P": self.P, "ld": self.ld,
+               "ms_per_step": round(ms_step, 4),
+               "GBps": round((self.sync_bytes + self.cons_bytes) / (ms_step * 1e-3) / 1e9, 1),
+               "group_sync": sync, "consensus": cons}
+        if self.idx == 1:
+            rec["note"] = ("cache-resident (33.6 MB stacks) and launch-bound: not an HBM figure; GB/s can exceed "
+                           "what HBM delivers")
+        return rec
+
+    def free(self):
+        for name in ("X", "V", "S", "Gs", "ws", "plan", "opt"):
+            setattr(self, name, None)
+        self.torch.cuda.empty_cache()
 
 
 def main() -> int:
@@ -108,8 +279,10 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=30,
                     help="untimed steps first; the first ~25 steps after start-up run about 8 %% slower")
-    ap.add_argument("--config", type=int, default=3,
-                    help="benchmark configuration 1-5 (default 3, the one the headline metric is quoted on)")
+    ap.add_argument("--config", type=int, default=0,
+                    help="time only this benchmark configuration (1-5) as the headline; default: configuration 3, "
+                         "the one the metric is quoted on, followed by a shorter run of all five (`all_configs`)")
+    ap.add_argument("--no-all-configs", action="store_true", help="skip the shorter runs of all five configurations")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--local-opt", choices=["none", "momentum", "swa", "both"], default="none",
                     help="time the extended step (momentum 0.9 / weight decay 5e-4 buffers and/or the SWA "
@@ -123,7 +296,8 @@ def main() -> int:
                          "the paper's Listing 1) as HIP graphs and time their replay; reported as `graph_replay`, "
                          "never as `value` (pays off where the step is launch-bound, i.e. configuration 1)")
     ap.add_argument("--dense-rows", action="store_true",
-                    help="leading dimension = P (rows not 256-byte aligned) instead of P rounded up to 64")
+                    help="leading dimension = P (rows start inside a cache line) instead of P rounded up to an "
+                         "odd multiple of 256 elements (rows on 1-KiB boundaries)")
     ap.add_argument("--probe-copy", type=int, default=0, metavar="N",
                     help="also launch the plain copy kernel N times on a stack-sized buffer before the "
                          "timed region (yardstick for bandwidth and for profiler counter scaling)")
@@ -139,92 +313,33 @@ def main() -> int:
 
     import torch
     import paper_2007_03298_amd as ds
-    from paper_2007_03298_amd import workloads as wl
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     dev = "cuda:0"
-    cfg = wl.CONFIGS[args.config]
-    W = cfg.W
-    if cfg.ragged:
-        # layer list of configuration 5: only the columns inside the segments are work
-        segs, ld, _ = wl.ragged_segments(cfg.seed)
-        P = sum(n for _, n in segs)
-        plan_bytes = ds.ds_ragged_plan_bytes(segs)
-        plan = torch.empty(plan_bytes, dtype=torch.uint8, device=dev)
-        packed = ds.pack_segments(segs)
-        plan_id = ds.ds_ragged_plan(packed, ld, ld, plan, plan_bytes)
-    else:
-        P = cfg.P
-        ld = P if args.dense_rows else wl.padded_ld(P)   # rows start on 256-byte boundaries
-    g_bytes = 2 if cfg.bf16_grads else 4
-    run = wl.Run(cfg, dev, P=ld, ld=ld)
-    X = run.init_params()
-    use_v = args.local_opt in ("momentum", "both")
-    use_s = args.local_opt in ("swa", "both")
-    V = torch.zeros_like(X) if use_v else None
-    S = X.clone() if use_s else None
-    opt = ds.local_opt(V, ld, 0.9, 5e-4 if use_v else 0.0, S, ld, 0.9) if (use_v or use_s) else None
-    n_grad = 2                                   # gradient stacks resident in HBM, used in turn
-    Gs = [run.gradients() for _ in range(n_grad)]
-    P_cons = ld if cfg.ragged else P              # ragged: the norm runs over the whole arena
-    ws_bytes = ds.ds_consensus_workspace_bytes(W, P_cons)
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
-    dev_out = torch.zeros(W, dtype=torch.float64, device=dev)
-    stream = torch.cuda.current_stream()
-
-    side = [torch.cuda.Stream() for _ in range(args.layerwise)] if args.layerwise > 0 else []
-    if side and not cfg.ragged:
-        print("bench.py: --layerwise needs --config 5", file=sys.stderr)
-        return 2
-    layer_done = [torch.cuda.Event() for _ in segs] if side else []
-
-    def layerwise(t, perm, off):
-        # Sec. V-A1: the backward hook of a layer updates it locally and starts its synchronisation
-        # without blocking; the pre-forward hook waits for that layer's event.  Layers become ready
-        # from the last to the first; here all are ready at once and the main stream waits for all.
-        fork = torch.cuda.Event()
-        fork.record(stream)
-        for st in side:
-            st.wait_event(fork)
-        G = Gs[t % n_grad]
-        for k, s in enumerate(reversed(range(len(segs)))):
-            o, n = segs[s]
-            st = side[k % len(side)]
-            ds.ds_group_sync_opt(X.data_ptr() + 4 * o, G.data_ptr() + g_bytes * o, ds.DS_BF16, n, ld, ld, W,
-                                 perm, off, cfg.lr, None, st)
-            layer_done[s].record(st)
-        for e in layer_done:
-            stream.wait_event(e)
-
-    def step(t, ev=None):
-        perm, off = ds.ds_partition(cfg.seed, t, W, cfg.sizes)
-        if ev:
-            ev[0].record(stream)
-        if side:
-            layerwise(t, perm, off)
-        elif cfg.ragged:
-            ds.ds_group_sync_ragged_opt(X, Gs[t % n_grad], ds.DS_BF16, packed, ld, ld, W, perm, off, cfg.lr, opt,
-                                        plan, plan_bytes, plan_id, stream)
-        else:
-            ds.ds_group_sync_opt(X, Gs[t % n_grad], ds.DS_F32, P, ld, ld, W, perm, off, cfg.lr, opt, stream)
-        if ev:
-            ev[1].record(stream)
-        ds.ds_consensus(X, P_cons, ld, W, dev_out, ws, ws_bytes, stream)
-        if ev:
-            ev[2].record(stream)
+    headline = args.config if args.config else 3
+    variant = args.local_opt != "none" or args.layerwise > 0 or args.dense_rows or args.graph > 0
+    want_all = not args.config and not args.no_all_configs and not variant
+    wk = Workload(headline, dev, args)
+    cfg, W, P, ld = wk.cfg, wk.W, wk.P, wk.ld
+    if args.layerwise > 0:
+        if not cfg.ragged:
+            print("bench.py: --layerwise needs --config 5", file=sys.stderr)
+            return 2
+        wk.use_layerwise(args.layerwise)
+    stream = wk.stream
 
     probe = None
     if args.probe_copy > 0:
         probe_copy = load_probe()
-        Y = torch.empty_like(X)
-        nbytes = X.numel() * 4
+        Y = torch.empty_like(wk.X)
+        nbytes = wk.X.numel() * 4
         pe = [torch.cuda.Event(enable_timing=True) for _ in range(args.probe_copy + 1)]
-        probe_copy(Y, X, nbytes, stream)
+        probe_copy(Y, wk.X, nbytes, stream)
         pe[0].record(stream)
         for k in range(args.probe_copy):
-            probe_copy(Y, X, nbytes, stream)
+            probe_copy(Y, wk.X, nbytes, stream)
             pe[k + 1].record(stream)
         torch.cuda.synchronize()
         pms = sum(pe[k].elapsed_time(pe[k + 1]) for k in range(args.probe_copy)) / args.probe_copy
@@ -232,40 +347,33 @@ def main() -> int:
                  "GBps": round(2.0 * nbytes / (pms * 1e-3) / 1e9, 1)}
         del Y
 
-    for t in range(args.warmup):
-        step(t)
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for k in range(args.steps):
-        step(args.warmup + k, events[k])
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
+    ms_step, sync_list, cons_list = wk.timed(args.warmup, args.steps)
+    sync_ms, cons_ms = statistics.fmean(sync_list), statistics.fmean(cons_list)
 
     # reported separately, never part of `value`: the norm from one row per group, valid because the
     # step has just made the members of every group identical
     perm, off = ds.ds_partition(cfg.seed, args.warmup + args.steps - 1, W, cfg.sizes)
     ge = [torch.cuda.Event(enable_timing=True) for _ in range(11)]
     dev_grouped = torch.zeros(W, dtype=torch.float64, device=dev)
-    ds.ds_consensus_grouped(X, P_cons, ld, W, perm, off, dev_grouped, ws, ws_bytes, stream)
+    ds.ds_consensus_grouped(wk.X, wk.P_cons, ld, W, perm, off, dev_grouped, wk.ws, wk.ws_bytes, stream)
     ge[0].record(stream)
     for k in range(10):
-        ds.ds_consensus_grouped(X, P_cons, ld, W, perm, off, dev_grouped, ws, ws_bytes, stream)
+        ds.ds_consensus_grouped(wk.X, wk.P_cons, ld, W, perm, off, dev_grouped, wk.ws, wk.ws_bytes, stream)
         ge[k + 1].record(stream)
     torch.cuda.synchronize()
     grouped_ms = sum(ge[k].elapsed_time(ge[k + 1]) for k in range(10)) / 10
-    grouped_gap = float((dev_grouped - dev_out).abs().max() / dev_out.abs().max().clamp_min(1e-300))
+    grouped_gap = float((dev_grouped - wk.dev_out).abs().max() / wk.dev_out.abs().max().clamp_min(1e-300))
 
     graph_replay = None
-    if args.graph > 0 and not side:
+    if args.graph > 0 and wk.layerwise is None:
         graphs = []
         for k in range(args.graph):
             g = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g):
-                stream = torch.cuda.current_stream()       # the capturing stream
-                step(k)
+                wk.stream = torch.cuda.current_stream()       # the capturing stream
+                wk.step(k)
             graphs.append(g)
-        stream = torch.cuda.current_stream()
+        wk.stream = stream
         for k in range(args.warmup):
             graphs[k % args.graph].replay()
         torch.cuda.synchronize()
@@ -276,15 +384,12 @@ def main() -> int:
         g_ms = (time.perf_counter() - g0) / args.steps * 1e3
         graph_replay = {"graphs": args.graph, "ms_per_step": round(g_ms, 4)}
 
-    ms_step = (t1 - t0) / args.steps * 1e3
-    sync_ms = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps
-    cons_ms = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
-    sync_bytes = (8.0 + g_bytes + 8.0 * use_v + 8.0 * use_s) * W * P
-    cons_bytes = 4.0 * W * P_cons
+    sync_bytes, cons_bytes = wk.sync_bytes, wk.cons_bytes
     sync_gbps = sync_bytes / (sync_ms * 1e-3) / 1e9
     cons_gbps = cons_bytes / (cons_ms * 1e-3) / 1e9
     value = (sync_bytes + cons_bytes) / (ms_step * 1e-3) / 1e9
-    d = dev_out.cpu()
+    d = wk.dev_out.cpu()
+    props = torch.cuda.get_device_properties(0)
 
     out = {
         "metric": "DS-Sync step (partition + fused group-sync + consensus) algorithmic HBM GB/s",
@@ -302,19 +407,22 @@ def main() -> int:
         "config": {"workload": cfg.name, "W": W, "group_size": cfg.group, "P": P, "ld": ld, "lr": cfg.lr,
                    "seed": cfg.seed, "bytes_per_step": int(sync_bytes + cons_bytes)},
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
-        "group_sync": {"ms": round(sync_ms, 4), "GBps": round(sync_gbps, 1),
-                       "pct_of_hbm_peak": round(100.0 * sync_gbps / HBM_PEAK_GBPS, 2)},
-        "consensus": {"ms": round(cons_ms, 4), "GBps": round(cons_gbps, 1),
-                      "pct_of_hbm_peak": round(100.0 * cons_gbps / HBM_PEAK_GBPS, 2),
-                      "max_deviation": float(d.max())},
-        "consensus_grouped": {"ms": round(grouped_ms, 4), "bytes_read": int(4.0 * len(cfg.sizes) * P_cons),
+        "group_sync": dict(spread(sync_list), GBps=round(sync_gbps, 1),
+                           pct_of_hbm_peak=round(100.0 * sync_gbps / HBM_PEAK_GBPS, 2)),
+        "consensus": dict(spread(cons_list), GBps=round(cons_gbps, 1),
+                          pct_of_hbm_peak=round(100.0 * cons_gbps / HBM_PEAK_GBPS, 2),
+                          max_deviation=float(d.max())),
+        "consensus_grouped": {"ms": round(grouped_ms, 4), "bytes_read": int(4.0 * len(cfg.sizes) * wk.P_cons),
                               "note": "one row per group; valid right after a group-sync; not in value",
                               "max_rel_gap_to_full": grouped_gap},
         "roofline": {"bound": "hbm", "kernel": "group_sync_kernel<float, flat>", "bytes_per_launch": int(sync_bytes),
                      "achieved": round(sync_gbps, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(sync_gbps / HBM_PEAK_GBPS, 4),
-                     "traffic": measured_traffic("group_sync_cfg%d_traffic.txt" % args.config,
-                                                 "cfg%d W=%d g=%d P=%d ld=%d" % (args.config, W, cfg.group, P, ld))},
+                     "traffic": measured_traffic("group_sync_cfg%d_traffic.txt" % headline,
+                                                 "cfg%d W=%d g=%d P=%d ld=%d" % (headline, W, cfg.group, P, ld))},
+        "device": {"name": props.name or getattr(props, "gcnArchName", ""), "arch": getattr(props, "gcnArchName", ""),
+                   "compute_units": props.multi_processor_count, "hbm_GiB": round(props.total_memory / 2**30, 1),
+                   "assumed_hbm_peak_GBps": HBM_PEAK_GBPS},
     }
     if probe is not None:
         out["probe_copy"] = probe
@@ -322,18 +430,59 @@ def main() -> int:
         graph_replay["GBps"] = round((sync_bytes + cons_bytes) / (graph_replay["ms_per_step"] * 1e-3) / 1e9, 1)
         graph_replay["note"] = "the same step replayed from HIP graphs, one per division of a periodic list; not in value"
         out["graph_replay"] = graph_replay
-    if opt is not None:
+    if wk.opt is not None:
         out["config"]["local_opt"] = args.local_opt
         out["roofline"]["kernel"] += " + " + args.local_opt
         out["roofline"]["traffic"] = None
-    if side:
-        out["config"]["layerwise_streams"] = len(side)
-        out["config"]["launches_per_step"] = len(segs)
+    if wk.layerwise is not None:
+        out["config"]["layerwise_streams"] = args.layerwise
+        out["config"]["launches_per_step"] = len(wk.segs)
+        out["roofline"]["traffic"] = None
     if cfg.ragged:
         out["dtype"] = "f32 (bf16 gradients)"
         out["roofline"]["kernel"] = "group_sync_kernel<bf16, ragged>"
-    if not args.no_cpu_baseline and not cfg.ragged and opt is None:
-        out["cpu_baseline"] = cpu_baseline(cfg, X, Gs[0])
+
+    cpu_inputs = None
+    if not args.no_cpu_baseline and not cfg.ragged and wk.opt is None and headline != 4:
+        import numpy as np
+        cpu_inputs = (cfg, np.ascontiguousarray(wk.X[:, :P].cpu().numpy()),
+                      np.ascontiguousarray(wk.Gs[0][:, :P].cpu().numpy()))
+
+    if want_all:
+        # a shorter run of every configuration (the headline one included, under the same short protocol)
+        steps_all, warm_all = max(10, min(args.steps, 30)), max(5, min(args.warmup, 15))
+        allc = {}
+        wk.free()
+        for idx in (1, 2, 3, 4, 5):
+            free, _ = torch.cuda.mem_get_info()
+            w2 = None
+            try:
+                w2 = Workload(idx, dev, args)
+                rec = w2.record(*w2.timed(warm_all, steps_all))
+                rec["steps"], rec["warmup"] = steps_all, warm_all
+                if idx == 5:
+                    # Sec. V-A1 / IV-A: the same step as one launch per layer on K side streams
+                    lw = {}
+                    for K in (1, 2):
+                        w2.use_layerwise(K)
+                        ms_k, sync_k, _ = w2.timed(3, 10, t0=1000)
+                        lw["streams_%d" % K] = dict(spread(sync_k), ms_per_step=round(ms_k, 4))
+                    w2.use_layerwise(0)
+                    lw["launches_per_step"] = len(w2.segs)
+                    lw["single_launch_ms"] = rec["group_sync"]["ms"]
+                    lw["note"] = "one launch per layer in reverse order with one event per layer; not in value"
+                    rec["layerwise"] = lw
+                allc[str(idx)] = rec
+            except torch.OutOfMemoryError:
+                allc[str(idx)] = {"skipped": "not enough free HBM (%.0f GB free)" % (free / 1e9)}
+            finally:
+                if w2 is not None:
+                    w2.free()
+                del w2
+        out["all_configs"] = allc
+
+    if cpu_inputs is not None:
+        out["cpu_baseline"] = cpu_baseline(*cpu_inputs)
     print(json.dumps(out), flush=True)
     return 0
 

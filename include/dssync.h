@@ -326,10 +326,10 @@ int ds_group_sync_ragged_opt(void* X, const void* G, int32_t g_dtype, const ds_s
  * Arithmetic: the column mean is formed in fp64 and split into an fp32 pair
  * hi + lo; the difference (x - hi) - lo and its square are fp32, so the
  * rounding error is relative to the difference itself and identical replicas
- * give exactly 0.  A lane sums the squares of at most 128 columns per worker
+ * give exactly 0.  A lane sums the squares of at most 256 columns per worker
  * in fp32 before the sum is widened; everything above that (across lanes,
- * wavefronts, workgroups) is fp64.  Relative error of a norm: below 4e-6 in the
- * worst case and about 3e-7 typically, whatever P.  The result is
+ * wavefronts, workgroups) is fp64.  Relative error of a norm: below 8e-6 in the
+ * worst case and about 5e-7 typically, whatever P.  The result is
  * deterministic (fixed reduction tree, no floating-point atomics).  X is read
  * once.
  *

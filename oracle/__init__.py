@@ -67,6 +67,8 @@ def _load():
                                          ctypes.c_int64, ctypes.c_int64, ctypes.c_int32]
         lib.orc_num_threads.restype = ctypes.c_int
         lib.orc_num_threads.argtypes = []
+        lib.orc_set_num_threads.restype = None
+        lib.orc_set_num_threads.argtypes = [ctypes.c_int]
         _lib = lib
     return _lib
 
@@ -205,3 +207,7 @@ def scaled_error(got: np.ndarray, want: np.ndarray, col0: int = 0, ncols: int | 
 
 def num_threads() -> int:
     return int(_load().orc_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    _load().orc_set_num_threads(int(n))

@@ -288,3 +288,14 @@ double orc_scaled_error(const float *got, const float *want, int64_t col0, int64
     }
     return bad ? NAN : worst;
 }
+
+/* Number of host threads the column loops use from now on (the benchmark's
+ * single-thread leg sets 1 and restores the previous value). */
+void orc_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    if (n >= 1) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}

@@ -11,13 +11,16 @@
 //     error is relative to the difference itself (and exactly zero for
 //     identical replicas); it is squared and summed into one fp32 accumulator
 //     per worker per lane;
-//   - a workgroup walks a run of consecutive column tiles; after every
-//     kFlushTiles tiles (and at the end) the lane accumulators are widened to
-//     fp64, reduced across the wavefront with lane shuffles and added to the
-//     wavefront's fp64 totals in LDS, so an fp32 accumulator never holds more
-//     than kFlushTiles * kVec <= 128 squares and the rounding error of a norm
-//     does not grow with the number of columns; at the end the 4 wavefronts'
-//     totals are added and written as one partial row per workgroup;
+//   - a workgroup walks a run of consecutive column tiles; at the end (and,
+//     for runs longer than kLaneColumns / kVec tiles, every that many tiles)
+//     the lane accumulators are widened to fp64, reduced across the wavefront
+//     with lane shuffles and added to the wavefront's fp64 totals in LDS, so an
+//     fp32 accumulator never holds more than 256 squares and the rounding
+//     error of a norm does not grow with the number of columns.  A widening
+//     in mid-run costs about 1 % of the pass each (the wavefront has no loads
+//     in flight meanwhile); with at most 8192 workgroups none is needed up to
+//     537 M columns; at the end the 4 wavefronts' totals are added and written
+//     as one partial row per workgroup;
 //   - a second kernel adds the partial rows in a fixed order and takes the
 //     square root.  No floating-point atomics: the result is deterministic.
 #include <hip/hip_runtime.h>
@@ -32,7 +35,9 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
 constexpr int kMaxBlocks = 8192;  // upper bound of the grid of the partial kernel
-constexpr int kFlushTiles = 32;   // tiles between two widenings of the fp32 lane accumulators
+// An fp32 lane accumulator takes the squares of at most this many columns per worker
+// before it is widened; with kVec columns per lane and tile that is kLaneColumns / kVec tiles.
+constexpr int kLaneColumns = 256;
 
 // Partial rows of ds_consensus_static: the largest workspace ds_consensus ever
 // asks for (kMaxBlocks rows of DS_MAX_W sums, 4 MiB), resident on every GPU
@@ -160,7 +165,7 @@ consensus_partial_kernel(const float* __restrict__ X, int64_t P, int64_t ld, int
             else
                 consensus_tile<kWPad, kVec, false, kGrouped>(acc, X, c, P, ld, W, tab, total_weight);
         }
-        if (++since == kFlushTiles || tile + 1 == tile1) {
+        if (++since == kLaneColumns / kVec || tile + 1 == tile1) {
             // lanes -> wavefront in fp64, added to the wavefront's totals; the fp32 sums start over
             since = 0;
 #pragma unroll
@@ -221,10 +226,13 @@ int launch_consensus(const float* x, int64_t P, int64_t ld, int32_t W, int32_t n
     const int64_t tile_cols = static_cast<int64_t>(kThreads) * vec;
     const int64_t n_tiles = (P + tile_cols - 1) / tile_cols;
     // consecutive tiles per workgroup: enough to amortise the end-of-block reduction,
-    // few enough to leave thousands of workgroups for the 256 CUs
+    // few enough to leave thousands of workgroups for the 256 CUs.  4096 workgroups are
+    // eight full rounds of the 512 that are resident at two per CU (the 64-row kernel);
+    // a count that leaves a partly filled last round measured 2-3 % slower.
     int64_t per_block = (n_tiles + kTargetBlocks - 1) / kTargetBlocks;
     if (per_block < 1) per_block = 1;
-    if ((n_tiles + per_block - 1) / per_block > kMaxBlocks) per_block = (n_tiles + kMaxBlocks - 1) / kMaxBlocks;
+    // runs longer than a lane accumulator takes are widened in mid-run: rather more workgroups
+    if (per_block > kLaneColumns / vec) per_block = (n_tiles + kMaxBlocks - 1) / kMaxBlocks;
     if (per_block > INT32_MAX) return DS_ERR_BAD_SHAPE;
     // at least one workgroup, so that P == 0 still writes a (zero) partial row
     const int64_t want_blocks = (n_tiles + per_block - 1) / per_block;

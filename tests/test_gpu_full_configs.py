@@ -228,3 +228,17 @@ def test_config5_ragged_full_size():
     np.testing.assert_allclose(d, mine, rtol=1e-5)
     print("  consensus max %.4f, worst relative gap to the oracle %.2e (its own trajectory: %.2e)" %
           (d.max(), np.abs(d / want - 1).max(), np.abs(d / mine - 1).max()), flush=True)
+
+
+def test_consensus_of_rows_too_long_for_one_lane_accumulator():
+    # beyond 8192 workgroups x 64 tiles x 1024 columns a workgroup's run is longer than an fp32 lane
+    # accumulator may take, and the kernel widens it in mid-run: 600 M columns of two workers
+    W, P = 2, 600_000_013
+    ld = ds.ds_padded_ld(P)
+    gen = torch.Generator(device=DEV).manual_seed(99)
+    X = torch.empty(W, ld, dtype=torch.float32, device=DEV).normal_(0, 0.02, generator=gen)
+    got = gpu_consensus(X, P, ld, W)
+    want = oracle_consensus_streamed(Stage(W), X, P)
+    assert want.min() > 0
+    np.testing.assert_allclose(got, want, rtol=1e-5)
+    print("  long rows: worst relative gap to the oracle %.2e" % np.abs(got / want - 1).max(), flush=True)
