@@ -236,6 +236,7 @@ class Workload:
     def timed(self, warmup, steps, t0=0):
         """`warmup` untimed steps, then `steps` timed ones: wall clock per step and per-kernel event times."""
         torch = self.torch
+        self.first_timed_t = t0 + warmup
         for t in range(warmup):
             self.step(t0 + t)
         events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
@@ -249,6 +250,43 @@ class Workload:
         cons_ms = [e[1].elapsed_time(e[2]) for e in events]
         return (b - a) / steps * 1e3, sync_ms, cons_ms
 
+    def fused_timed(self, warmup, steps, t0=5000):
+        """The step and the norms of its result in one pass (ds_group_sync_consensus): reported
+        separately, never in `value`, whose consensus term stays the full second pass."""
+        torch, ds, cfg = self.torch, self.ds, self.cfg
+        if cfg.ragged or self.opt is not None:
+            return None
+        n_groups = len(cfg.sizes)
+        need = ds.ds_group_sync_consensus_workspace_bytes(self.P, n_groups)
+        ws = torch.empty(need, dtype=torch.uint8, device=self.X.device)
+        out = torch.zeros(self.W, dtype=torch.float64, device=self.X.device)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+        for k in range(warmup + steps):
+            t = t0 + k
+            perm, off = ds.ds_partition(cfg.seed, t, self.W, cfg.sizes)
+            if k == warmup:
+                torch.cuda.synchronize()
+                a = time.perf_counter()
+                ev[0].record(self.stream)
+            ds.ds_group_sync_consensus(self.X, self.Gs[t % len(self.Gs)], self.g_dtype, self.P, self.ld, self.ld,
+                                       self.W, perm, off, cfg.lr, out, ws, need, self.stream)
+            if k >= warmup:
+                ev[k - warmup + 1].record(self.stream)
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - a) / steps * 1e3
+        ms = [ev[k].elapsed_time(ev[k + 1]) for k in range(steps)]
+        # the full pass on the same state, for the gap between the two ways to the norms
+        ds.ds_consensus(self.X, self.P_cons, self.ld, self.W, self.dev_out, self.ws, self.ws_bytes, self.stream)
+        torch.cuda.synchronize()
+        gap = float((out - self.dev_out).abs().max() / self.dev_out.abs().max().clamp_min(1e-300))
+        rec = spread(ms)
+        rec.update(ms_per_step=round(wall, 4), bytes_moved=int(self.sync_bytes),
+                   GBps=round(self.sync_bytes / (rec["ms_median"] * 1e-3) / 1e9, 1),
+                   max_rel_gap_to_full_consensus=gap,
+                   note="ds_group_sync_consensus: step and norms in one pass over the stacks (the norms come from "
+                        "the group means, the stack is not read again); not in value")
+        return rec
+
     def record(self, ms_step, sync_ms, cons_ms):
         """Figures of one configuration for `all_configs`."""
         sync, cons = spread(sync_ms), spread(cons_ms)
@@ -258,6 +296,10 @@ class Workload:
                     bytes_per_launch=int(self.sync_bytes))
         cons.update(GBps=round(cons_gbps, 1), frac=round(cons_gbps / HBM_PEAK_GBPS, 4),
                     bytes_per_launch=int(self.cons_bytes))
+        # the two resident gradient stacks are used in turn: where the stacks lie in HBM shows at 35 GB per stack
+        n = len(self.Gs)
+        sync["ms_by_gradient_stack"] = [round(statistics.fmean(sync_ms[(j - self.first_timed_t) % n::n]), 4)
+                                        for j in range(n)]
         rec = {"workload": self.cfg.name, "W": self.W, "group_size": self.cfg.group, "P": self.P, "ld": self.ld,
                "ms_per_step": round(ms_step, 4),
                "GBps": round((self.sync_bytes + self.cons_bytes) / (ms_step * 1e-3) / 1e9, 1),
@@ -460,6 +502,9 @@ def main() -> int:
                 w2 = Workload(idx, dev, args)
                 rec = w2.record(*w2.timed(warm_all, steps_all))
                 rec["steps"], rec["warmup"] = steps_all, warm_all
+                fused = w2.fused_timed(5, steps_all)
+                if fused is not None:
+                    rec["fused_step_and_consensus"] = fused
                 if idx == 5:
                     # Sec. V-A1 / IV-A: the same step as one launch per layer on K side streams
                     lw = {}

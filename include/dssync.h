@@ -389,6 +389,42 @@ int ds_consensus_grouped(const void* X, int64_t P, int64_t ld, int32_t W, const 
                          size_t workspace_bytes, void* stream);
 
 /*
+ * ds_group_sync_consensus -- ds_group_sync and ds_consensus of its result in ONE
+ * pass over the stacks.
+ *
+ * Paper: Listing 1 (optimizer.step(), Average(model, group)) and Sec. IV-B2
+ * (Lemma 1's left side).  After the step the members of a group hold the
+ * group's mean m_k, so with n_k = |g_k|
+ *     xbar[p] = (1/W) * sum_k n_k * m_k[p];   dev_out[i] = || m_{g(i)} - xbar ||_2
+ * are the consensus norms of the updated stack, and the kernel that takes the
+ * step has every m_k in registers: a wavefront owns 256 columns of ALL groups,
+ * takes the step group by group, forms xbar in fp64 and sums the squared
+ * differences as ds_consensus does (fp32 pair for the mean, fp32 squares, fp64
+ * above the lane).  The replica stack is not read a second time: 12 (10 with
+ * bf16 gradients) instead of 16 (14) bytes per (worker, column) for step plus
+ * norms, and two launches instead of three.  X afterwards is bit for bit what
+ * ds_group_sync leaves; dev_out agrees with ds_consensus of it to rounding.
+ * When to use it: the pass walks all 2W row streams of the stacks at once, and
+ * HBM sustains less over that many streams than over the 2|g| of ds_group_sync
+ * (measured 5.3 against 6.4 TB/s at W = 32, groups of 8), so it wins where
+ * launches and latency dominate - stacks that fit the last-level cache, e.g.
+ * 8 x 1 M parameters: 30 us against 45 us for ds_group_sync + ds_consensus -
+ * while on large stacks ds_group_sync followed by ds_consensus_grouped is the
+ * faster way to the same norms.
+ *
+ *   workspace  dev, 16-byte aligned, >= ds_group_sync_consensus_workspace_bytes(P, n_groups)
+ *              bytes (one fp64 partial sum per group and tile of 256 columns), overwritten
+ *   dev_out    dev fp64 [W], written (zeros if P == 0)
+ * Other arguments as ds_group_sync (plain step, fp32 or bf16 gradients).
+ * Errors: those of ds_group_sync, DS_ERR_WORKSPACE, DS_ERR_ALIGN for dev_out.
+ */
+size_t ds_group_sync_consensus_workspace_bytes(int64_t P, int32_t n_groups);
+
+int ds_group_sync_consensus(void* X, const void* G, int32_t g_dtype, int64_t P, int64_t ldx, int64_t ldg,
+                            int32_t W, const int32_t* perm, const int32_t* off, int32_t n_groups, float lr,
+                            double* dev_out, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * ds_padded_ld -- the leading dimension (row pitch, in elements) the kernels
  * run fastest with for rows of P elements: P rounded up to an odd multiple of
  * 256.  Data layout only, not a step of the method (the paper stacks the

@@ -25,6 +25,7 @@ DS_MAX_COLUMNS = ((1 << 26) - 1) * 256
 EXPORTS = ("ds_status_string", "ds_partition", "ds_pattern", "ds_pattern_period", "ds_pattern_check", "ds_group_sync",
            "ds_ragged_plan_bytes", "ds_ragged_plan", "ds_group_sync_ragged", "ds_group_sync_opt",
            "ds_group_sync_ragged_opt", "ds_consensus_workspace_bytes", "ds_consensus", "ds_consensus_static", "ds_consensus_grouped",
+           "ds_group_sync_consensus_workspace_bytes", "ds_group_sync_consensus",
            "ds_padded_ld")
 
 
@@ -87,6 +88,11 @@ def _load() -> ctypes.CDLL:
     lib.ds_consensus_static.argtypes = [vp, i64, i64, i32, vp, vp]
     lib.ds_consensus_grouped.restype = ctypes.c_int
     lib.ds_consensus_grouped.argtypes = [vp, i64, i64, i32, i32p, i32p, i32, vp, vp, sz, vp]
+    lib.ds_group_sync_consensus_workspace_bytes.restype = sz
+    lib.ds_group_sync_consensus_workspace_bytes.argtypes = [i64, i32]
+    lib.ds_group_sync_consensus.restype = ctypes.c_int
+    lib.ds_group_sync_consensus.argtypes = [vp, vp, i32, i64, i64, i64, i32, i32p, i32p, i32, ctypes.c_float, vp, vp,
+                                            sz, vp]
     lib.ds_padded_ld.restype = i64
     lib.ds_padded_ld.argtypes = [i64]
     return lib
@@ -297,6 +303,18 @@ def ds_consensus_grouped(X, P: int, ld: int, W: int, perm, off, dev_out, workspa
     perm, off = _i32(perm), _i32(off)
     _check(_lib.ds_consensus_grouped(_addr(X), P, ld, W, _i32p(perm), _i32p(off), len(off) - 1, _addr(dev_out),
                                      _addr(workspace), workspace_bytes, _stream(stream)), "ds_consensus_grouped")
+
+
+def ds_group_sync_consensus_workspace_bytes(P: int, n_groups: int) -> int:
+    return int(_lib.ds_group_sync_consensus_workspace_bytes(int(P), int(n_groups)))
+
+
+def ds_group_sync_consensus(X, G, g_dtype: int, P: int, ldx: int, ldg: int, W: int, perm, off, lr: float,
+                            dev_out, workspace, workspace_bytes: int, stream=None) -> None:
+    perm, off = _i32(perm), _i32(off)
+    _check(_lib.ds_group_sync_consensus(_addr(X), _addr(G), g_dtype, P, ldx, ldg, W, _i32p(perm), _i32p(off),
+                                        len(off) - 1, lr, _addr(dev_out), _addr(workspace), workspace_bytes,
+                                        _stream(stream)), "ds_group_sync_consensus")
 
 
 def ds_padded_ld(P: int) -> int:

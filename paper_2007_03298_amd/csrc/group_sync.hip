@@ -200,11 +200,15 @@ __device__ __forceinline__ void store_members(const f32x4& mean, float* xt, int6
 }
 
 // One tile of one group.  kFull: the tile has all kSyncTileCols columns.
+// mean_out receives the lane's four column means (zeros for a lane beyond the
+// tile), tail_out the mean of the single column a lane handles at a ragged end
+// (zero for every other lane): what the fused consensus needs.
 template <typename GT, bool kFull, bool kOpt, bool kHasV, bool kHasS>
 __device__ __forceinline__ void sync_tile(float* xt, const GT* gt, int len, int64_t ldx, int64_t ldg,
-                                          const Extras& ex, const PartitionArg& part, int first, int n, float lr) {
+                                          const Extras& ex, const PartitionArg& part, int first, int n, float lr,
+                                          f32x4& mean_out, float& tail_out) {
     constexpr int kChunk = kSyncLoadsPerLane / 2;   // members per round of loads
-    const int lane = static_cast<int>(threadIdx.x);
+    const int lane = static_cast<int>(threadIdx.x) & (kSyncThreads - 1);
     const int col = lane * 4;
     const bool live = kFull || col + 4 <= len;
     f32x4 sum = {0.f, 0.f, 0.f, 0.f};
@@ -223,6 +227,8 @@ __device__ __forceinline__ void sync_tile(float* xt, const GT* gt, int len, int6
     static_assert(kChunk == 8, "the remainder switch lists 1..7 members");
     const float nf = static_cast<float>(n);
     sum = sum / nf;
+    mean_out = sum;
+    tail_out = 0.f;
     if (!kHasS) {
         for (int m = first; m < end; ++m) store_members<1, kFull, false>(sum, xt, ldx, ex, part, m, col, live);
     } else {
@@ -249,6 +255,7 @@ __device__ __forceinline__ void sync_tile(float* xt, const GT* gt, int len, int6
                 acc += x - lr * d;
             }
             acc = acc / nf;
+            tail_out = acc;
             for (int m = first; m < end; ++m) {
                 const int64_t row = packed_byte(part.perm, m);
                 xt[row * ldx + c] = acc;
@@ -294,10 +301,122 @@ group_sync_kernel(float* __restrict__ X, const GT* __restrict__ G, int64_t ldx, 
     if (kHasS) ex.s += start;
     const int first = packed_byte(part.off, static_cast<int>(group_id));
     const int n = packed_byte(part.off, static_cast<int>(group_id) + 1) - first;
+    f32x4 mean;
+    float tail;
     if (len == kTileCols)
-        sync_tile<GT, true, kOpt, kHasV, kHasS>(X + start, G + start, len, ldx, ldg, ex, part, first, n, lr);
+        sync_tile<GT, true, kOpt, kHasV, kHasS>(X + start, G + start, len, ldx, ldg, ex, part, first, n, lr, mean, tail);
     else
-        sync_tile<GT, false, kOpt, kHasV, kHasS>(X + start, G + start, len, ldx, ldg, ex, part, first, n, lr);
+        sync_tile<GT, false, kOpt, kHasV, kHasS>(X + start, G + start, len, ldx, ldg, ex, part, first, n, lr, mean, tail);
+}
+
+// ---------------------------------------------------------------- step and consensus norms in one pass
+//
+// Right after a step every member of a group holds the group's mean, so the
+// consensus norms (Sec. IV-B2, left side of Lemma 1) follow from the means the
+// step has in registers anyway: with m_k the mean of group k and n_k its size,
+//     xbar[p] = (1/W) sum_k n_k m_k[p],    d_i = || m_{g(i)} - xbar ||_2 .
+// A wavefront owns a tile of 256 columns of ALL groups: it takes the step group
+// after group exactly as above, parks each group's means in LDS (each lane
+// reads back only what it wrote, so no barrier is needed), then forms xbar per
+// column in fp64, splits it into an fp32 pair and sums ((m_k - hi) - lo)^2 over
+// its columns - the arithmetic of the consensus kernel - reduces that across
+// the lanes in fp64 and writes one partial sum per (group, tile).  A second,
+// small kernel adds the partial sums of each group in a fixed order, takes the
+// square root and hands the norm to every member.  The replica stack is not
+// read a second time.
+// What it costs: the walk is tile-major, so all 2W row streams of the stacks
+// are open at once instead of the 2|g| of the group-major step, and HBM
+// sustains less over more concurrent streams - at best 5.3-5.4 TB/s (3 to 5
+// wavefronts per CU) against 6.4 for the plain step on 32 x 25.6 M fp32
+// stacks.  Also measured there: the loads of group k+1 issued
+// ahead of the stores of group k, so that the in-order memory counter does not
+// make them wait for those stores (no gain, 200 registers), and one wavefront
+// per group in a workgroup that exchanges the means behind a barrier (30 %
+// slower: the wavefronts of a workgroup move in lock step).  The fused pass
+// therefore pays where launches and latency dominate (stacks that fit the
+// last-level cache); on large stacks the plain step followed by
+// ds_consensus_grouped is faster.
+constexpr int kFusedLdsPerGroup = kSyncThreads * (16 + 4);   // bytes: a 4-vector and a tail value per lane
+
+template <typename GT>
+__global__ void __launch_bounds__(kSyncThreads)
+group_sync_consensus_kernel(float* __restrict__ X, const GT* __restrict__ G, int64_t ldx, int64_t ldg, int64_t P,
+                            PartitionArg part, int n_groups, int n_workers, float lr, int64_t n_tiles,
+                            double* __restrict__ partial) {
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    f32x4* means = reinterpret_cast<f32x4*>(lds_raw);
+    float* tails = reinterpret_cast<float*>(means + static_cast<size_t>(n_groups) * kSyncThreads);
+    const int lane = static_cast<int>(threadIdx.x);
+    const int64_t tile_id = blockIdx.x;
+    const int64_t start = tile_id * kSyncTileCols;
+    const int64_t left = P - start;
+    const int len = left < kSyncTileCols ? static_cast<int>(left) : kSyncTileCols;
+    const Extras none = {nullptr, nullptr, 0, 0, 0.f, 0.f, 0.f};
+    for (int k = 0; k < n_groups; ++k) {
+        const int first = packed_byte(part.off, k);
+        const int n = packed_byte(part.off, k + 1) - first;
+        f32x4 mean;
+        float tail;
+        if (len == kSyncTileCols)
+            sync_tile<GT, true, false, false, false>(X + start, G + start, len, ldx, ldg, none, part, first, n, lr, mean, tail);
+        else
+            sync_tile<GT, false, false, false, false>(X + start, G + start, len, ldx, ldg, none, part, first, n, lr, mean, tail);
+        means[k * kSyncThreads + lane] = mean;
+        tails[k * kSyncThreads + lane] = tail;
+    }
+    // column means over all workers, fp64: the 4 vector columns and the tail column of this lane
+    double xbar[5] = {0.0, 0.0, 0.0, 0.0, 0.0};
+    for (int k = 0; k < n_groups; ++k) {
+        const double w = static_cast<double>(packed_byte(part.off, k + 1) - packed_byte(part.off, k));
+        const f32x4 m = means[k * kSyncThreads + lane];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) xbar[e] += w * static_cast<double>(m[e]);
+        xbar[4] += w * static_cast<double>(tails[k * kSyncThreads + lane]);
+    }
+    float hi[5], lo[5];
+#pragma unroll
+    for (int e = 0; e < 5; ++e) {
+        const double m = xbar[e] / static_cast<double>(n_workers);
+        hi[e] = static_cast<float>(m);
+        lo[e] = static_cast<float>(m - static_cast<double>(hi[e]));
+    }
+    for (int k = 0; k < n_groups; ++k) {
+        const f32x4 m = means[k * kSyncThreads + lane];
+        float sq = 0.f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float d = (m[e] - hi[e]) - lo[e];
+            sq = __builtin_fmaf(d, d, sq);
+        }
+        const float dt = (tails[k * kSyncThreads + lane] - hi[4]) - lo[4];
+        sq = __builtin_fmaf(dt, dt, sq);
+        double v = static_cast<double>(sq);
+#pragma unroll
+        for (int mask = 32; mask >= 1; mask >>= 1) v += __shfl_xor(v, mask, 64);
+        if (lane == 0) partial[static_cast<int64_t>(k) * n_tiles + tile_id] = v;
+    }
+}
+
+constexpr int kNormThreads = 256;
+
+// One workgroup per group: fixed-order sum of the group's partial sums, square
+// root, and the norm goes to every member of the group.
+__global__ void __launch_bounds__(kNormThreads)
+group_norm_kernel(const double* __restrict__ partial, int64_t n_tiles, PartitionArg part, double* __restrict__ out) {
+    __shared__ double buf[kNormThreads];
+    const int k = static_cast<int>(blockIdx.x);
+    const double* mine = partial + static_cast<int64_t>(k) * n_tiles;
+    double v = 0.0;
+    for (int64_t t = threadIdx.x; t < n_tiles; t += kNormThreads) v += mine[t];
+    buf[threadIdx.x] = v;
+    __syncthreads();
+    for (int half = kNormThreads / 2; half >= 1; half >>= 1) {
+        if (static_cast<int>(threadIdx.x) < half) buf[threadIdx.x] += buf[threadIdx.x + half];
+        __syncthreads();
+    }
+    const int first = packed_byte(part.off, k);
+    const int n = packed_byte(part.off, k + 1) - first;
+    if (static_cast<int>(threadIdx.x) < n) out[packed_byte(part.perm, first + static_cast<int>(threadIdx.x))] = sqrt(buf[0]);
 }
 
 // ---------------------------------------------------------------- ragged plan
@@ -545,6 +664,56 @@ extern "C" int ds_group_sync_opt(void* X, const void* G, int32_t g_dtype, int64_
                                  int64_t ldg, int32_t W, const int32_t* perm, const int32_t* off,
                                  int32_t n_groups, float lr, const ds_local_opt* opt, void* stream) {
     return group_sync_flat(X, G, g_dtype, P, ldx, ldg, W, perm, off, n_groups, lr, opt, stream);
+}
+
+extern "C" size_t ds_group_sync_consensus_workspace_bytes(int64_t P, int32_t n_groups) {
+    if (P < 0 || P > DS_MAX_COLUMNS || n_groups < 1 || n_groups > DS_MAX_W) return 0;
+    const int64_t n_tiles = (P + kSyncTileCols - 1) / kSyncTileCols;
+    const int64_t entries = n_tiles * n_groups;
+    return static_cast<size_t>(entries < 2 ? 2 : entries) * sizeof(double);   // never 0 for valid arguments
+}
+
+extern "C" int ds_group_sync_consensus(void* X, const void* G, int32_t g_dtype, int64_t P, int64_t ldx,
+                                       int64_t ldg, int32_t W, const int32_t* perm, const int32_t* off,
+                                       int32_t n_groups, float lr, double* dev_out, void* workspace,
+                                       size_t workspace_bytes, void* stream) {
+    int rc = check_stacks(X, G, g_dtype, ldx, ldg);
+    if (rc != DS_OK) return rc;
+    if (!dev_out) return DS_ERR_NULL;
+    if (P < 0 || ldx < P || ldg < P || P > DS_MAX_COLUMNS) return DS_ERR_BAD_SHAPE;
+    if ((reinterpret_cast<uintptr_t>(dev_out) & 7u) != 0) return DS_ERR_ALIGN;
+    PartitionArg part;
+    int32_t max_size = 0;
+    rc = ds::pack_partition(W, perm, off, n_groups, &part, &max_size);
+    if (rc != DS_OK) return rc;
+    if (!workspace || !ds::aligned16(workspace) ||
+        workspace_bytes < ds_group_sync_consensus_workspace_bytes(P, n_groups))
+        return DS_ERR_WORKSPACE;
+    ds::DeviceInfo dev;
+    rc = ds::device_info(&dev);
+    if (rc != DS_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int64_t n_tiles = (P + kSyncTileCols - 1) / kSyncTileCols;
+    double* partial = static_cast<double*>(workspace);
+    if (n_tiles > 0) {
+        // LDS: the parked means, or more if the occupancy rule asks for fewer wavefronts per CU
+        unsigned lds = static_cast<unsigned>(n_groups) * kFusedLdsPerGroup;
+        const unsigned pad = occupancy_pad(max_size, g_dtype == DS_BF16, false, n_tiles * n_groups, dev);
+        if (pad > lds) lds = pad;
+        const dim3 grid(static_cast<uint32_t>(n_tiles)), block(kSyncThreads);
+        hipError_t err;
+        if (g_dtype == DS_F32)
+            err = ds::launch_kernel(group_sync_consensus_kernel<float>, grid, block, lds, st, static_cast<float*>(X),
+                                    static_cast<const float*>(G), ldx, ldg, P, part, n_groups, W, lr, n_tiles, partial);
+        else
+            err = ds::launch_kernel(group_sync_consensus_kernel<uint16_t>, grid, block, lds, st, static_cast<float*>(X),
+                                    static_cast<const uint16_t*>(G), ldx, ldg, P, part, n_groups, W, lr, n_tiles,
+                                    partial);
+        if (err != hipSuccess) return DS_ERR_HIP;
+    }
+    const hipError_t err = ds::launch_kernel(group_norm_kernel, dim3(static_cast<uint32_t>(n_groups)),
+                                             dim3(kNormThreads), 0, st, partial, n_tiles, part, dev_out);
+    return err == hipSuccess ? DS_OK : DS_ERR_HIP;
 }
 
 extern "C" size_t ds_ragged_plan_bytes(const ds_segment* segs, int32_t S) {

@@ -232,6 +232,27 @@ def test_consensus_argument_errors():
     assert status(ws=3 * B + 8) == -8
 
 
+def test_fused_step_and_consensus_argument_errors():
+    need = ds.ds_group_sync_consensus_workspace_bytes(16, 2)
+    assert need >= 16 and ds.ds_group_sync_consensus_workspace_bytes(1000, 3) == 4 * 3 * 8
+    assert ds.ds_group_sync_consensus_workspace_bytes(-1, 2) == 0
+    assert ds.ds_group_sync_consensus_workspace_bytes(16, 0) == 0
+    assert ds.ds_group_sync_consensus_workspace_bytes(ds.DS_MAX_COLUMNS + 4, 2) == 0
+
+    def status(X=A, G=B, P=16, ld=16, W=8, perm=PERM8, off=OFF8, out=2 * B, ws=3 * B, ws_bytes=need):
+        with pytest.raises(ds.DsError) as e:
+            ds.ds_group_sync_consensus(X, G, 0, P, ld, ld, W, perm, off, 0.1, out, ws, ws_bytes, stream=0)
+        return e.value.status
+    assert status(X=0) == -1
+    assert status(out=0) == -1
+    assert status(out=2 * B + 4) == -6
+    assert status(P=17) == -5
+    assert status(perm=[0, 1, 2, 3, 4, 5, 6, 6]) == -4
+    assert status(ws=0) == -8
+    assert status(ws=3 * B + 8) == -8
+    assert status(ws_bytes=need - 1) == -8
+
+
 def test_static_scratch_consensus_checks_its_arguments_like_the_workspace_one():
     lib = ctypes.CDLL(binding.LIB_PATH)
     lib.ds_consensus_static.restype = ctypes.c_int
