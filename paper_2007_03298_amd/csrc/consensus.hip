@@ -80,10 +80,14 @@ __device__ __forceinline__ int table_byte(const uint32_t* words, int i) {
 // back to back).
 // n_rows rows take part; kGrouped: row i is tab.row[i] with weight tab.weight[i]
 // and total_weight = number of workers, else row i with weight 1.
-template <int kWPad, int kVec, bool kFull, bool kGrouped>
+// kPow2: the number of workers is a power of two and inv_pow2 its reciprocal -
+// the fp64 division is a long sequence (3 % of the pass at 64 workers) and
+// multiplying is then exactly dividing; any other count is divided properly, so
+// that the mean of identical replicas is the replica itself to the last bit.
+template <int kWPad, int kVec, bool kFull, bool kGrouped, bool kPow2>
 __device__ __forceinline__ void consensus_tile(float (&acc)[kWPad], const float* __restrict__ X, int64_t c,
                                                int64_t P, int64_t ld, int W, const RowTable& tab,
-                                               int total_weight) {
+                                               int total_weight, double inv_pow2) {
     typedef typename VecOf<kVec>::type vec_t;
     vec_t row[kWPad];
 #pragma unroll
@@ -115,11 +119,14 @@ __device__ __forceinline__ void consensus_tile(float (&acc)[kWPad], const float*
     // mean as an unevaluated fp32 pair hi + lo (|lo| <= ulp(hi)/2): subtracting
     // hi, then lo, in fp32 leaves an error that is relative to the difference
     // itself, and is exactly 0 when every row equals the mean
+    // a power-of-two worker count divides exactly by multiplication (the fp64 division is a long
+    // sequence: 3 % of the pass at 64 workers); any other count is divided properly, so that the mean
+    // of identical replicas is the replica itself to the last bit
     const double wd = static_cast<double>(kGrouped ? total_weight : W);
     float hi[kVec], lo[kVec];
 #pragma unroll
     for (int e = 0; e < kVec; ++e) {
-        const double m = mean[e] / wd;
+        const double m = kPow2 ? mean[e] * inv_pow2 : mean[e] / wd;
         hi[e] = static_cast<float>(m);
         lo[e] = static_cast<float>(m - static_cast<double>(hi[e]));
     }
@@ -135,10 +142,10 @@ __device__ __forceinline__ void consensus_tile(float (&acc)[kWPad], const float*
     }
 }
 
-template <int kWPad, int kVec, bool kGrouped>
+template <int kWPad, int kVec, bool kGrouped, bool kPow2>
 __global__ void __launch_bounds__(kThreads)
 consensus_partial_kernel(const float* __restrict__ X, int64_t P, int64_t ld, int W, int tiles_per_block,
-                         double* __restrict__ partial, RowTable tab, int total_weight) {
+                         double* __restrict__ partial, RowTable tab, int total_weight, double inv_pow2) {
     constexpr int kTileCols = kThreads * kVec;
     float acc[kWPad];
 #pragma unroll
@@ -158,12 +165,12 @@ consensus_partial_kernel(const float* __restrict__ X, int64_t P, int64_t ld, int
     for (int64_t tile = tile0; tile < tile1; ++tile) {
         const int64_t c = tile * kTileCols + static_cast<int64_t>(threadIdx.x) * kVec;
         if ((tile + 1) * kTileCols <= P) {
-            consensus_tile<kWPad, kVec, true, kGrouped>(acc, X, c, P, ld, W, tab, total_weight);
+            consensus_tile<kWPad, kVec, true, kGrouped, kPow2>(acc, X, c, P, ld, W, tab, total_weight, inv_pow2);
         } else if (c < P) {
             if (c + kVec <= P)
-                consensus_tile<kWPad, kVec, true, kGrouped>(acc, X, c, P, ld, W, tab, total_weight);
+                consensus_tile<kWPad, kVec, true, kGrouped, kPow2>(acc, X, c, P, ld, W, tab, total_weight, inv_pow2);
             else
-                consensus_tile<kWPad, kVec, false, kGrouped>(acc, X, c, P, ld, W, tab, total_weight);
+                consensus_tile<kWPad, kVec, false, kGrouped, kPow2>(acc, X, c, P, ld, W, tab, total_weight, inv_pow2);
         }
         if (++since == kLaneColumns / kVec || tile + 1 == tile1) {
             // lanes -> wavefront in fp64, added to the wavefront's totals; the fp32 sums start over
@@ -238,26 +245,40 @@ int launch_consensus(const float* x, int64_t P, int64_t ld, int32_t W, int32_t n
     const int64_t want_blocks = (n_tiles + per_block - 1) / per_block;
     const int n_blocks = static_cast<int>(want_blocks < 1 ? 1 : want_blocks);
     const int tpb = static_cast<int>(per_block);
+    // 1/W when W is a power of two (then multiplying is exactly dividing), else 0: the kernel divides
+    const double inv_pow2 = (W & (W - 1)) == 0 ? 1.0 / static_cast<double>(W) : 0.0;
     const dim3 grid(static_cast<uint32_t>(n_blocks)), block(kThreads);
     hipError_t err;
+#define DS_PARTIAL(WP, V) \
+    err = inv_pow2 != 0.0 ? ds::launch_kernel(consensus_partial_kernel<WP, V, kGrouped, true>, grid, block, 0, st, x, P, ld, \
+                                              n_rows, tpb, partial, tab, W, inv_pow2) \
+                          : ds::launch_kernel(consensus_partial_kernel<WP, V, kGrouped, false>, grid, block, 0, st, x, P, ld, \
+                                              n_rows, tpb, partial, tab, W, inv_pow2)
     switch (w_pad) {
-        case 8: err = ds::launch_kernel(consensus_partial_kernel<8, 4, kGrouped>, grid, block, 0, st, x, P, ld, n_rows, tpb, partial, tab, W); break;
-        case 16: err = ds::launch_kernel(consensus_partial_kernel<16, 4, kGrouped>, grid, block, 0, st, x, P, ld, n_rows, tpb, partial, tab, W); break;
-        case 32: err = ds::launch_kernel(consensus_partial_kernel<32, 2, kGrouped>, grid, block, 0, st, x, P, ld, n_rows, tpb, partial, tab, W); break;
-        default: err = ds::launch_kernel(consensus_partial_kernel<64, 2, kGrouped>, grid, block, 0, st, x, P, ld, n_rows, tpb, partial, tab, W); break;
+        case 8: DS_PARTIAL(8, 4); break;
+        case 16: DS_PARTIAL(16, 4); break;
+        case 32: DS_PARTIAL(32, 2); break;
+        default: DS_PARTIAL(64, 2); break;
     }
+#undef DS_PARTIAL
     if (err != hipSuccess) return DS_ERR_HIP;
     err = ds::launch_kernel(consensus_final_kernel, dim3(static_cast<uint32_t>(W)), block, 0, st, partial, n_blocks, w_pad,
                             dev_out, tab);
     return err == hipSuccess ? DS_OK : DS_ERR_HIP;
 }
 
-int check_consensus_args(const void* X, int64_t P, int64_t ld, int32_t W, const double* dev_out, const void* workspace,
-                         size_t workspace_bytes) {
+int check_consensus_stack(const void* X, int64_t P, int64_t ld, int32_t W, const double* dev_out) {
     if (!X || !dev_out) return DS_ERR_NULL;
     if (W < 1 || W > DS_MAX_W) return DS_ERR_BAD_W;
     if (P < 0 || ld < P || P > DS_MAX_COLUMNS) return DS_ERR_BAD_SHAPE;
     if (!ds::aligned16(X) || ld % 4 != 0 || (reinterpret_cast<uintptr_t>(dev_out) & 7u) != 0) return DS_ERR_ALIGN;
+    return DS_OK;
+}
+
+int check_consensus_args(const void* X, int64_t P, int64_t ld, int32_t W, const double* dev_out, const void* workspace,
+                         size_t workspace_bytes) {
+    const int rc = check_consensus_stack(X, P, ld, W, dev_out);
+    if (rc != DS_OK) return rc;
     if (!workspace || !ds::aligned16(workspace) || workspace_bytes < ds_consensus_workspace_bytes(W, P))
         return DS_ERR_WORKSPACE;
     return DS_OK;
@@ -299,9 +320,7 @@ double* scratch_on_current_device() {
 
 extern "C" int ds_consensus_static(const void* X, int64_t P, int64_t ld, int32_t W, double* dev_out,
                                    void* stream) {
-    // the workspace checks of ds_consensus are met by construction: any non-NULL aligned stand-in passes them
-    alignas(16) static const char stand_in = 0;
-    const int rc = check_consensus_args(X, P, ld, W, dev_out, &stand_in, ds_consensus_workspace_bytes(W, P));
+    const int rc = check_consensus_stack(X, P, ld, W, dev_out);
     if (rc != DS_OK) return rc;
     static_assert(sizeof(scratch) >= static_cast<size_t>(kMaxBlocks) * 64 * sizeof(double),
                   "the array holds the largest workspace ds_consensus asks for");
