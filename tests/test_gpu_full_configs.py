@@ -242,3 +242,56 @@ def test_consensus_of_rows_too_long_for_one_lane_accumulator():
     assert want.min() > 0
     np.testing.assert_allclose(got, want, rtol=1e-5)
     print("  long rows: worst relative gap to the oracle %.2e" % np.abs(got / want - 1).max(), flush=True)
+
+
+def test_step_and_consensus_with_more_than_2_32_columns():
+    # column indices beyond 32 bits inside one row (the five configurations stay below 2^32 columns, although
+    # their stacks exceed 2^32 elements): two workers in one group, every column against the oracle
+    W, P = 2, (1 << 32) + (1 << 20) + 777
+    ld = ds.ds_padded_ld(P)
+    free, _ = torch.cuda.mem_get_info()
+    if free < 3 * W * ld * 4 + (4 << 30):
+        pytest.skip("needs %.0f GB of free HBM" % (3 * W * ld * 4 / 1e9))
+    gen = torch.Generator(device=DEV).manual_seed(232)
+    X = torch.empty(W, ld, dtype=torch.float32, device=DEV).normal_(0, 0.02, generator=gen)
+    G = torch.empty(W, ld, dtype=torch.float32, device=DEV).normal_(generator=gen)
+    Xb = X.clone()
+    stage, own = Stage(W), OracleState()
+    perm, off = [1, 0], [0, 2]
+    ds.ds_group_sync(X, G, ds.DS_F32, P, ld, ld, W, perm, off, 0.01)
+    e_step, _ = sweep_step(stage, Xb, G, X, [(0, P)], perm, off, 0.01, own)
+    assert e_step <= TOL_F32
+    members_identical_on_device(X, P, perm, off)
+    assert torch.equal(X[:, P:], Xb[:, P:])
+    assert np.array_equal(gpu_consensus(X, P, ld, W), np.zeros(W))          # one group: consensus reached
+    d = gpu_consensus(Xb, P, ld, W)                                         # the random start: far from it
+    want = oracle_consensus_streamed(stage, Xb, P)
+    np.testing.assert_allclose(d, want, rtol=1e-5)
+    print("  2^32+ columns: step err %.2e, consensus gap %.2e" % (e_step, np.abs(d / want - 1).max()), flush=True)
+
+
+def test_step_at_the_largest_column_count_one_launch_covers():
+    # DS_MAX_COLUMNS: the grid is at HIP's limit of 2^32 threads along x; one worker (a group of one is
+    # plain SGD on its own gradient), bf16 gradients, every column against the oracle
+    W, P = 1, ds.DS_MAX_COLUMNS
+    ld = P
+    free, _ = torch.cuda.mem_get_info()
+    need = 2 * P * 4 + P * 2 + (6 << 30)
+    if free < need:
+        pytest.skip("needs %.0f GB of free HBM" % (need / 1e9))
+    gen = torch.Generator(device=DEV).manual_seed(226)
+    X = torch.empty(W, ld, dtype=torch.float32, device=DEV)
+    G = torch.empty(W, ld, dtype=torch.bfloat16, device=DEV)
+    step = 1 << 30
+    for c0 in range(0, P, step):                       # filled in slices: torch's generators work on 32-bit counts
+        X[:, c0:c0 + step].normal_(0, 0.02, generator=gen)
+        G[:, c0:c0 + step] = torch.empty(W, min(step, P - c0), dtype=torch.float32, device=DEV).normal_(generator=gen)
+    Xb = X.clone()
+    ds.ds_group_sync(X, G, ds.DS_BF16, P, ld, ld, W, [0], [0, 1], 0.01)
+    with pytest.raises(ds.DsError) as e:               # four columns more are refused on the host
+        ds.ds_group_sync(X, G, ds.DS_BF16, P + 4, ld + 4, ld + 4, W, [0], [0, 1], 0.01)
+    assert e.value.status == -5
+    e_step, _ = sweep_step(Stage(W), Xb, G, X, [(0, P)], [0], [0, 1], 0.01, OracleState())
+    print("  %d columns: step err %.2e" % (P, e_step), flush=True)
+    assert e_step <= TOL_F32
+    assert not torch.equal(X[:, -4096:], Xb[:, -4096:])                    # the last tile was processed
