@@ -169,7 +169,7 @@ class Workload:
         import torch
         import paper_2007_03298_amd as ds
         from paper_2007_03298_amd import workloads as wl
-        self.torch, self.ds, self.idx = torch, ds, idx
+        self.torch, self.ds, self.idx, self.wl = torch, ds, idx, wl
         cfg = self.cfg = wl.CONFIGS[idx]
         self.W = W = cfg.W
         if cfg.ragged:
@@ -286,6 +286,67 @@ class Workload:
                    note="ds_group_sync_consensus: step and norms in one pass over the stacks (the norms come from "
                         "the group means, the stack is not read again); not in value")
         return rec
+
+    def tiled_timed(self, warmup, steps, t0=7000):
+        """The same step and consensus pass on TILED stacks (the W pieces of a 256-column tile
+        contiguous; ds_group_sync_tiled, ds_consensus_tiled, ds_group_sync_consensus_tiled).
+        Another layout of the same workload: reported separately, never in `value`.
+        Converts this workload's stacks, so it runs last."""
+        torch, ds, cfg, wl = self.torch, self.ds, self.cfg, self.wl
+        if cfg.ragged or self.opt is not None:
+            return None
+        W, P, st = self.W, self.P, self.stream
+        ts = W * wl.TILE
+        self.X = wl.to_tiled(self.X, P)
+        for j in range(len(self.Gs)):
+            self.Gs[j] = wl.to_tiled(self.Gs[j], P)
+            torch.cuda.empty_cache()
+        n_groups = len(cfg.sizes)
+        need = ds.ds_group_sync_consensus_workspace_bytes(P, n_groups)
+        ws2 = torch.empty(need, dtype=torch.uint8, device=self.X.device)
+        out2 = torch.zeros(W, dtype=torch.float64, device=self.X.device)
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+        fe = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+        for k in range(warmup + steps):
+            perm, off = ds.ds_partition(cfg.seed, t0 + k, W, cfg.sizes)
+            if k == warmup:
+                torch.cuda.synchronize()
+                a = time.perf_counter()
+            e = ev[k - warmup] if k >= warmup else None
+            if e:
+                e[0].record(st)
+            ds.ds_group_sync_tiled(self.X, self.Gs[k % len(self.Gs)], self.g_dtype, P, ts, ts, W, perm, off, cfg.lr,
+                                   None, st)
+            if e:
+                e[1].record(st)
+            ds.ds_consensus_tiled(self.X, P, ts, W, self.dev_out, self.ws, self.ws_bytes, st)
+            if e:
+                e[2].record(st)
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - a) / steps * 1e3
+        for k in range(5 + steps):
+            perm, off = ds.ds_partition(cfg.seed, t0 + 500 + k, W, cfg.sizes)
+            if k == 5:
+                fe[0].record(st)
+            ds.ds_group_sync_consensus_tiled(self.X, self.Gs[k % len(self.Gs)], self.g_dtype, P, ts, ts, W, perm, off,
+                                             cfg.lr, out2, ws2, need, st)
+            if k >= 5:
+                fe[k - 4].record(st)
+        ds.ds_consensus_tiled(self.X, P, ts, W, self.dev_out, self.ws, self.ws_bytes, st)
+        torch.cuda.synchronize()
+        gap = float((out2 - self.dev_out).abs().max() / self.dev_out.abs().max().clamp_min(1e-300))
+        sync = spread([e[0].elapsed_time(e[1]) for e in ev])
+        cons = spread([e[1].elapsed_time(e[2]) for e in ev])
+        fused = spread([fe[k].elapsed_time(fe[k + 1]) for k in range(steps)])
+        sync["GBps"] = round(self.sync_bytes / (sync["ms"] * 1e-3) / 1e9, 1)
+        cons["GBps"] = round(4.0 * W * P / (cons["ms"] * 1e-3) / 1e9, 1)
+        fused["GBps"] = round(self.sync_bytes / (fused["ms_median"] * 1e-3) / 1e9, 1)
+        fused["max_rel_gap_to_full_consensus"] = gap
+        return {"tile_stride": ts, "ms_per_step": round(wall, 4),
+                "GBps": round((self.sync_bytes + 4.0 * W * P) / (wall * 1e-3) / 1e9, 1),
+                "group_sync": sync, "consensus": cons, "fused_step_and_consensus": fused,
+                "note": "the same workload with the stacks stored tile by tile (element (i, p) at "
+                        "(p // 256) * W * 256 + i * 256 + p % 256): another layout, not in value"}
 
     def record(self, ms_step, sync_ms, cons_ms):
         """Figures of one configuration for `all_configs`."""
@@ -517,6 +578,9 @@ def main() -> int:
                     lw["single_launch_ms"] = rec["group_sync"]["ms"]
                     lw["note"] = "one launch per layer in reverse order with one event per layer; not in value"
                     rec["layerwise"] = lw
+                tiled = w2.tiled_timed(5, steps_all)
+                if tiled is not None:
+                    rec["tiled_layout"] = tiled
                 allc[str(idx)] = rec
             except torch.OutOfMemoryError:
                 allc[str(idx)] = {"skipped": "not enough free HBM (%.0f GB free)" % (free / 1e9)}

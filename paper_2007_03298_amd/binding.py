@@ -25,7 +25,8 @@ DS_MAX_COLUMNS = ((1 << 26) - 1) * 256
 EXPORTS = ("ds_status_string", "ds_partition", "ds_pattern", "ds_pattern_period", "ds_pattern_check", "ds_group_sync",
            "ds_ragged_plan_bytes", "ds_ragged_plan", "ds_group_sync_ragged", "ds_group_sync_opt",
            "ds_group_sync_ragged_opt", "ds_consensus_workspace_bytes", "ds_consensus", "ds_consensus_static", "ds_consensus_grouped",
-           "ds_group_sync_consensus_workspace_bytes", "ds_group_sync_consensus",
+           "ds_group_sync_consensus_workspace_bytes", "ds_group_sync_consensus", "ds_tiled_elements",
+           "ds_group_sync_tiled", "ds_consensus_tiled", "ds_group_sync_consensus_tiled",
            "ds_padded_ld")
 
 
@@ -93,6 +94,15 @@ def _load() -> ctypes.CDLL:
     lib.ds_group_sync_consensus.restype = ctypes.c_int
     lib.ds_group_sync_consensus.argtypes = [vp, vp, i32, i64, i64, i64, i32, i32p, i32p, i32, ctypes.c_float, vp, vp,
                                             sz, vp]
+    lib.ds_tiled_elements.restype = i64
+    lib.ds_tiled_elements.argtypes = [i64, i32]
+    lib.ds_group_sync_tiled.restype = ctypes.c_int
+    lib.ds_group_sync_tiled.argtypes = [vp, vp, i32, i64, i64, i64, i32, i32p, i32p, i32, ctypes.c_float, optp, vp]
+    lib.ds_consensus_tiled.restype = ctypes.c_int
+    lib.ds_consensus_tiled.argtypes = [vp, i64, i64, i32, vp, vp, sz, vp]
+    lib.ds_group_sync_consensus_tiled.restype = ctypes.c_int
+    lib.ds_group_sync_consensus_tiled.argtypes = [vp, vp, i32, i64, i64, i64, i32, i32p, i32p, i32, ctypes.c_float,
+                                                  vp, vp, sz, vp]
     lib.ds_padded_ld.restype = i64
     lib.ds_padded_ld.argtypes = [i64]
     return lib
@@ -315,6 +325,33 @@ def ds_group_sync_consensus(X, G, g_dtype: int, P: int, ldx: int, ldg: int, W: i
     _check(_lib.ds_group_sync_consensus(_addr(X), _addr(G), g_dtype, P, ldx, ldg, W, _i32p(perm), _i32p(off),
                                         len(off) - 1, lr, _addr(dev_out), _addr(workspace), workspace_bytes,
                                         _stream(stream)), "ds_group_sync_consensus")
+
+
+def ds_tiled_elements(P: int, W: int) -> int:
+    return int(_lib.ds_tiled_elements(int(P), int(W)))
+
+
+def ds_group_sync_tiled(X, G, g_dtype: int, P: int, tile_stride_x: int, tile_stride_g: int, W: int, perm, off,
+                        lr: float, opt: ds_local_opt | None = None, stream=None) -> None:
+    perm, off = _i32(perm), _i32(off)
+    _check(_lib.ds_group_sync_tiled(_addr(X), _addr(G), g_dtype, P, tile_stride_x, tile_stride_g, W, _i32p(perm),
+                                    _i32p(off), len(off) - 1, lr, ctypes.byref(opt) if opt is not None else None,
+                                    _stream(stream)), "ds_group_sync_tiled")
+
+
+def ds_consensus_tiled(X, P: int, tile_stride: int, W: int, dev_out, workspace, workspace_bytes: int,
+                       stream=None) -> None:
+    _check(_lib.ds_consensus_tiled(_addr(X), P, tile_stride, W, _addr(dev_out), _addr(workspace), workspace_bytes,
+                                   _stream(stream)), "ds_consensus_tiled")
+
+
+def ds_group_sync_consensus_tiled(X, G, g_dtype: int, P: int, tile_stride_x: int, tile_stride_g: int, W: int, perm,
+                                  off, lr: float, dev_out, workspace, workspace_bytes: int, stream=None) -> None:
+    perm, off = _i32(perm), _i32(off)
+    _check(_lib.ds_group_sync_consensus_tiled(_addr(X), _addr(G), g_dtype, P, tile_stride_x, tile_stride_g, W,
+                                              _i32p(perm), _i32p(off), len(off) - 1, lr, _addr(dev_out),
+                                              _addr(workspace), workspace_bytes, _stream(stream)),
+           "ds_group_sync_consensus_tiled")
 
 
 def ds_padded_ld(P: int) -> int:

@@ -86,21 +86,25 @@ __device__ __forceinline__ int table_byte(const uint32_t* words, int i) {
 // that the mean of identical replicas is the replica itself to the last bit.
 template <int kWPad, int kVec, bool kFull, bool kGrouped, bool kPow2>
 __device__ __forceinline__ void consensus_tile(float (&acc)[kWPad], const float* __restrict__ X, int64_t c,
-                                               int64_t P, int64_t ld, int W, const RowTable& tab,
+                                               int64_t P, int64_t ld, int64_t tile_stride, int W, const RowTable& tab,
                                                int total_weight, double inv_pow2) {
     typedef typename VecOf<kVec>::type vec_t;
     vec_t row[kWPad];
+    // column c of row r is at (c / 256) * tile_stride + r * ld + c % 256: row-major stacks pass
+    // tile_stride = 256 (that is r * ld + c), tiled stacks ld = 256 and the stride of their blocks
+    static_assert(256 % kVec == 0, "a lane's columns stay inside one 256-column tile");
+    const float* base = X + (c >> 8) * tile_stride + (c & 255);
 #pragma unroll
     for (int i = 0; i < kWPad; ++i) {
         if (i < W) {
             const int64_t r = kGrouped ? table_byte(tab.row, i) : i;
             if (kFull) {
-                row[i] = __builtin_nontemporal_load(reinterpret_cast<const vec_t*>(X + r * ld + c));
+                row[i] = __builtin_nontemporal_load(reinterpret_cast<const vec_t*>(base + r * ld));
             } else {
                 // last, partial vector of the row: columns at or beyond P count as 0
                 // in every row, which adds nothing to any deviation
 #pragma unroll
-                for (int e = 0; e < kVec; ++e) row[i][e] = (c + e < P) ? X[r * ld + c + e] : 0.f;
+                for (int e = 0; e < kVec; ++e) row[i][e] = (c + e < P) ? base[r * ld + e] : 0.f;
             }
         }
     }
@@ -144,8 +148,9 @@ __device__ __forceinline__ void consensus_tile(float (&acc)[kWPad], const float*
 
 template <int kWPad, int kVec, bool kGrouped, bool kPow2>
 __global__ void __launch_bounds__(kThreads)
-consensus_partial_kernel(const float* __restrict__ X, int64_t P, int64_t ld, int W, int tiles_per_block,
-                         double* __restrict__ partial, RowTable tab, int total_weight, double inv_pow2) {
+consensus_partial_kernel(const float* __restrict__ X, int64_t P, int64_t ld, int64_t tile_stride, int W,
+                         int tiles_per_block, double* __restrict__ partial, RowTable tab, int total_weight,
+                         double inv_pow2) {
     constexpr int kTileCols = kThreads * kVec;
     float acc[kWPad];
 #pragma unroll
@@ -165,12 +170,12 @@ consensus_partial_kernel(const float* __restrict__ X, int64_t P, int64_t ld, int
     for (int64_t tile = tile0; tile < tile1; ++tile) {
         const int64_t c = tile * kTileCols + static_cast<int64_t>(threadIdx.x) * kVec;
         if ((tile + 1) * kTileCols <= P) {
-            consensus_tile<kWPad, kVec, true, kGrouped, kPow2>(acc, X, c, P, ld, W, tab, total_weight, inv_pow2);
+            consensus_tile<kWPad, kVec, true, kGrouped, kPow2>(acc, X, c, P, ld, tile_stride, W, tab, total_weight, inv_pow2);
         } else if (c < P) {
             if (c + kVec <= P)
-                consensus_tile<kWPad, kVec, true, kGrouped, kPow2>(acc, X, c, P, ld, W, tab, total_weight, inv_pow2);
+                consensus_tile<kWPad, kVec, true, kGrouped, kPow2>(acc, X, c, P, ld, tile_stride, W, tab, total_weight, inv_pow2);
             else
-                consensus_tile<kWPad, kVec, false, kGrouped, kPow2>(acc, X, c, P, ld, W, tab, total_weight, inv_pow2);
+                consensus_tile<kWPad, kVec, false, kGrouped, kPow2>(acc, X, c, P, ld, tile_stride, W, tab, total_weight, inv_pow2);
         }
         if (++since == kLaneColumns / kVec || tile + 1 == tile1) {
             // lanes -> wavefront in fp64, added to the wavefront's totals; the fp32 sums start over
@@ -226,8 +231,8 @@ void set_byte(uint32_t* words, int i, int value) { words[i >> 2] |= static_cast<
 
 // n_rows rows are read (W for the plain norm, n_groups for the grouped one); W outputs.
 template <bool kGrouped>
-int launch_consensus(const float* x, int64_t P, int64_t ld, int32_t W, int32_t n_rows, const RowTable& tab,
-                     double* dev_out, double* partial, hipStream_t st) {
+int launch_consensus(const float* x, int64_t P, int64_t ld, int64_t tile_stride, int32_t W, int32_t n_rows,
+                     const RowTable& tab, double* dev_out, double* partial, hipStream_t st) {
     const int w_pad = padded_w(n_rows);
     const int vec = w_pad >= 32 ? 2 : 4;   // keeps the rows of one lane within 64 registers
     const int64_t tile_cols = static_cast<int64_t>(kThreads) * vec;
@@ -251,9 +256,9 @@ int launch_consensus(const float* x, int64_t P, int64_t ld, int32_t W, int32_t n
     hipError_t err;
 #define DS_PARTIAL(WP, V) \
     err = inv_pow2 != 0.0 ? ds::launch_kernel(consensus_partial_kernel<WP, V, kGrouped, true>, grid, block, 0, st, x, P, ld, \
-                                              n_rows, tpb, partial, tab, W, inv_pow2) \
+                                              tile_stride, n_rows, tpb, partial, tab, W, inv_pow2) \
                           : ds::launch_kernel(consensus_partial_kernel<WP, V, kGrouped, false>, grid, block, 0, st, x, P, ld, \
-                                              n_rows, tpb, partial, tab, W, inv_pow2)
+                                              tile_stride, n_rows, tpb, partial, tab, W, inv_pow2)
     switch (w_pad) {
         case 8: DS_PARTIAL(8, 4); break;
         case 16: DS_PARTIAL(16, 4); break;
@@ -292,7 +297,22 @@ extern "C" int ds_consensus(const void* X, int64_t P, int64_t ld, int32_t W, dou
     if (rc != DS_OK) return rc;
     RowTable tab = {};
     for (int32_t i = 0; i < W; ++i) set_byte(tab.src, i, i);
-    return launch_consensus<false>(static_cast<const float*>(X), P, ld, W, W, tab, dev_out,
+    return launch_consensus<false>(static_cast<const float*>(X), P, ld, 256, W, W, tab, dev_out,
+                                   static_cast<double*>(workspace), static_cast<hipStream_t>(stream));
+}
+
+extern "C" int ds_consensus_tiled(const void* X, int64_t P, int64_t tile_stride, int32_t W, double* dev_out,
+                                  void* workspace, size_t workspace_bytes, void* stream) {
+    if (!X || !dev_out) return DS_ERR_NULL;
+    if (W < 1 || W > DS_MAX_W) return DS_ERR_BAD_W;
+    if (P < 0 || P > DS_MAX_COLUMNS || tile_stride < static_cast<int64_t>(W) * 256) return DS_ERR_BAD_SHAPE;
+    if (!ds::aligned16(X) || tile_stride % 256 != 0 || (reinterpret_cast<uintptr_t>(dev_out) & 7u) != 0)
+        return DS_ERR_ALIGN;
+    if (!workspace || !ds::aligned16(workspace) || workspace_bytes < ds_consensus_workspace_bytes(W, P))
+        return DS_ERR_WORKSPACE;
+    RowTable tab = {};
+    for (int32_t i = 0; i < W; ++i) set_byte(tab.src, i, i);
+    return launch_consensus<false>(static_cast<const float*>(X), P, 256, tile_stride, W, W, tab, dev_out,
                                    static_cast<double*>(workspace), static_cast<hipStream_t>(stream));
 }
 
@@ -328,7 +348,7 @@ extern "C" int ds_consensus_static(const void* X, int64_t P, int64_t ld, int32_t
     if (!partial) return DS_ERR_HIP;
     RowTable tab = {};
     for (int32_t i = 0; i < W; ++i) set_byte(tab.src, i, i);
-    return launch_consensus<false>(static_cast<const float*>(X), P, ld, W, W, tab, dev_out, partial,
+    return launch_consensus<false>(static_cast<const float*>(X), P, ld, 256, W, W, tab, dev_out, partial,
                                    static_cast<hipStream_t>(stream));
 }
 
@@ -347,6 +367,6 @@ extern "C" int ds_consensus_grouped(const void* X, int64_t P, int64_t ld, int32_
         set_byte(tab.weight, k, off[k + 1] - off[k]);
         for (int32_t q = off[k]; q < off[k + 1]; ++q) set_byte(tab.src, perm[q], k);
     }
-    return launch_consensus<true>(static_cast<const float*>(X), P, ld, W, n_groups, tab, dev_out,
+    return launch_consensus<true>(static_cast<const float*>(X), P, ld, 256, W, n_groups, tab, dev_out,
                                   static_cast<double*>(workspace), static_cast<hipStream_t>(stream));
 }

@@ -131,8 +131,22 @@ __device__ __forceinline__ float load_grad1(const uint16_t* p) {
 struct Extras {
     float* v;
     float* s;
-    int64_t ldv, lds;
+    int64_t ldv, lds;       // row strides
+    int64_t tsv, tss;       // tile strides (tiled stacks only; see TileWalk)
     float momentum, weight_decay, factor;
+};
+
+// Tiled stacks (kTiled instances of the kernels): the W pieces of a 256-column
+// tile are one contiguous block, so tile t of a stack is at base + t * tile
+// stride (>= W*256) and the row stride handed on to sync_tile is 256.  The grid
+// is 1-D, tiles * groups with the group running fastest (tile_major = number of
+// groups), so that consecutive workgroups walk the blocks front to back.  The
+// row-major instances never read this argument: their tile t is at column
+// 256 * t of every row and their grid is (tiles, groups), whose consecutive
+// workgroups walk the rows of one group.
+struct TileWalk {
+    int64_t tsx, tsg;
+    int32_t tile_major;
 };
 
 // Adds the locally updated parameters of kCount members (perm positions
@@ -265,14 +279,19 @@ __device__ __forceinline__ void sync_tile(float* xt, const GT* gt, int len, int6
     }
 }
 
-template <typename GT, bool kRagged, bool kOpt, bool kHasV, bool kHasS>
+template <typename GT, bool kRagged, bool kTiled, bool kOpt, bool kHasV, bool kHasS>
 __global__ void __launch_bounds__(kSyncThreads)
 group_sync_kernel(float* __restrict__ X, const GT* __restrict__ G, int64_t ldx, int64_t ldg,
                   int64_t P, const Tile* __restrict__ tiles, uint64_t plan_id, int32_t plan_entries,
-                  PartitionArg part, float lr, Extras ex) {
+                  PartitionArg part, float lr, Extras ex, TileWalk walk) {
     static_assert(kOpt || (!kHasV && !kHasS), "extra state implies the extended step");
+    static_assert(!(kRagged && kTiled), "segment lists address row-major stacks");
     constexpr int kTileCols = kSyncTileCols;
-    const uint32_t tile_id = blockIdx.x, group_id = blockIdx.y;
+    uint32_t tile_id = blockIdx.x, group_id = blockIdx.y;
+    if (kTiled) {
+        group_id = blockIdx.x % static_cast<uint32_t>(walk.tile_major);
+        tile_id = blockIdx.x / static_cast<uint32_t>(walk.tile_major);
+    }
     int64_t start;
     int32_t len;
     if (kRagged) {
@@ -297,16 +316,27 @@ group_sync_kernel(float* __restrict__ X, const GT* __restrict__ G, int64_t ldx, 
         const int64_t left = P - start;
         len = left < kTileCols ? static_cast<int32_t>(left) : kTileCols;
     }
-    if (kHasV) ex.v += start;
-    if (kHasS) ex.s += start;
+    float* xt;
+    const GT* gt;
+    if (!kTiled) {
+        xt = X + start;
+        gt = G + start;
+        if (kHasV) ex.v += start;
+        if (kHasS) ex.s += start;
+    } else {
+        xt = X + static_cast<int64_t>(tile_id) * walk.tsx;
+        gt = G + static_cast<int64_t>(tile_id) * walk.tsg;
+        if (kHasV) ex.v += static_cast<int64_t>(tile_id) * ex.tsv;
+        if (kHasS) ex.s += static_cast<int64_t>(tile_id) * ex.tss;
+    }
     const int first = packed_byte(part.off, static_cast<int>(group_id));
     const int n = packed_byte(part.off, static_cast<int>(group_id) + 1) - first;
     f32x4 mean;
     float tail;
     if (len == kTileCols)
-        sync_tile<GT, true, kOpt, kHasV, kHasS>(X + start, G + start, len, ldx, ldg, ex, part, first, n, lr, mean, tail);
+        sync_tile<GT, true, kOpt, kHasV, kHasS>(xt, gt, len, ldx, ldg, ex, part, first, n, lr, mean, tail);
     else
-        sync_tile<GT, false, kOpt, kHasV, kHasS>(X + start, G + start, len, ldx, ldg, ex, part, first, n, lr, mean, tail);
+        sync_tile<GT, false, kOpt, kHasV, kHasS>(xt, gt, len, ldx, ldg, ex, part, first, n, lr, mean, tail);
 }
 
 // ---------------------------------------------------------------- step and consensus norms in one pass
@@ -324,25 +354,26 @@ group_sync_kernel(float* __restrict__ X, const GT* __restrict__ G, int64_t ldx, 
 // small kernel adds the partial sums of each group in a fixed order, takes the
 // square root and hands the norm to every member.  The replica stack is not
 // read a second time.
-// What it costs: the walk is tile-major, so all 2W row streams of the stacks
-// are open at once instead of the 2|g| of the group-major step, and HBM
-// sustains less over more concurrent streams - at best 5.3-5.4 TB/s (3 to 5
-// wavefronts per CU) against 6.4 for the plain step on 32 x 25.6 M fp32
-// stacks.  Also measured there: the loads of group k+1 issued
-// ahead of the stores of group k, so that the in-order memory counter does not
-// make them wait for those stores (no gain, 200 registers), and one wavefront
-// per group in a workgroup that exchanges the means behind a barrier (30 %
-// slower: the wavefronts of a workgroup move in lock step).  The fused pass
-// therefore pays where launches and latency dominate (stacks that fit the
-// last-level cache); on large stacks the plain step followed by
-// ds_consensus_grouped is faster.
+// What it costs: a wavefront takes its groups one after the other, each a round
+// of loads, the arithmetic and a round of stores, and the loads of the next
+// group queue behind those stores in the in-order memory counter.  At best
+// 5.3-5.4 TB/s (3 to 5 wavefronts per CU) against 6.4 for the plain step on
+// 32 x 25.6 M fp32 stacks.  The number of row streams open at once (2W in this
+// tile-major walk against 2|g| in the group-major step) is not what holds it
+// back: on tiled stacks, where the walk reads two sequential streams, it runs
+// at the same 5.4 TB/s.  Also measured: the loads of group k+1 issued ahead of
+// the stores of group k (no gain, 200 registers), and one wavefront per group
+// in a workgroup that exchanges the means behind a barrier (30 % slower: the
+// wavefronts of a workgroup move in lock step).  The fused pass therefore pays
+// where launches and latency dominate (stacks that fit the last-level cache);
+// on large stacks the plain step followed by ds_consensus_grouped is faster.
 constexpr int kFusedLdsPerGroup = kSyncThreads * (16 + 4);   // bytes: a 4-vector and a tail value per lane
 
 template <typename GT>
 __global__ void __launch_bounds__(kSyncThreads)
 group_sync_consensus_kernel(float* __restrict__ X, const GT* __restrict__ G, int64_t ldx, int64_t ldg, int64_t P,
                             PartitionArg part, int n_groups, int n_workers, float lr, int64_t n_tiles,
-                            double* __restrict__ partial) {
+                            double* __restrict__ partial, TileWalk walk) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     f32x4* means = reinterpret_cast<f32x4*>(lds_raw);
     float* tails = reinterpret_cast<float*>(means + static_cast<size_t>(n_groups) * kSyncThreads);
@@ -351,16 +382,18 @@ group_sync_consensus_kernel(float* __restrict__ X, const GT* __restrict__ G, int
     const int64_t start = tile_id * kSyncTileCols;
     const int64_t left = P - start;
     const int len = left < kSyncTileCols ? static_cast<int>(left) : kSyncTileCols;
-    const Extras none = {nullptr, nullptr, 0, 0, 0.f, 0.f, 0.f};
+    const Extras none = {nullptr, nullptr, 0, 0, 0, 0, 0.f, 0.f, 0.f};
+    float* xt = X + tile_id * walk.tsx;
+    const GT* gt = G + tile_id * walk.tsg;
     for (int k = 0; k < n_groups; ++k) {
         const int first = packed_byte(part.off, k);
         const int n = packed_byte(part.off, k + 1) - first;
         f32x4 mean;
         float tail;
         if (len == kSyncTileCols)
-            sync_tile<GT, true, false, false, false>(X + start, G + start, len, ldx, ldg, none, part, first, n, lr, mean, tail);
+            sync_tile<GT, true, false, false, false>(xt, gt, len, ldx, ldg, none, part, first, n, lr, mean, tail);
         else
-            sync_tile<GT, false, false, false, false>(X + start, G + start, len, ldx, ldg, none, part, first, n, lr, mean, tail);
+            sync_tile<GT, false, false, false, false>(xt, gt, len, ldx, ldg, none, part, first, n, lr, mean, tail);
         means[k * kSyncThreads + lane] = mean;
         tails[k * kSyncThreads + lane] = tail;
     }
@@ -544,9 +577,10 @@ struct LaunchShape {
     int64_t n_live_tiles;    // workgroups along x that find columns
     int32_t largest;         // largest group
     int32_t n_groups;
+    TileWalk walk;           // flat: where the tiles are and in which order they are walked
 };
 
-template <typename GT, bool kRagged, bool kOpt, bool kHasV, bool kHasS>
+template <typename GT, bool kRagged, bool kTiled, bool kOpt, bool kHasV, bool kHasS>
 int launch_one(float* X, const GT* G, int64_t ldx, int64_t ldg, const LaunchShape& sh, const PartitionArg& part,
                float lr, const Extras& ex, hipStream_t st) {
     ds::DeviceInfo dev;
@@ -554,54 +588,60 @@ int launch_one(float* X, const GT* G, int64_t ldx, int64_t ldg, const LaunchShap
     if (rc != DS_OK) return rc;
     const int64_t grid_x = kRagged ? sh.plan_entries * (kPlanTileCols / kSyncTileCols)
                                    : (sh.P + kSyncTileCols - 1) / kSyncTileCols;
-    const dim3 grid(static_cast<uint32_t>(grid_x), static_cast<uint32_t>(sh.n_groups), 1);
+    const bool tile_major = kTiled;
+    const dim3 grid(static_cast<uint32_t>(tile_major ? grid_x * sh.n_groups : grid_x),
+                    static_cast<uint32_t>(tile_major ? 1 : sh.n_groups), 1);
     const unsigned lds_pad = occupancy_pad(sh.largest, sizeof(GT) == 2, kHasV, sh.n_live_tiles * sh.n_groups, dev);
-    const hipError_t err = ds::launch_kernel(group_sync_kernel<GT, kRagged, kOpt, kHasV, kHasS>, grid,
+    const hipError_t err = ds::launch_kernel(group_sync_kernel<GT, kRagged, kTiled, kOpt, kHasV, kHasS>, grid,
                                              dim3(kSyncThreads, 1, 1), lds_pad, st, X, G, ldx, ldg, sh.P, sh.plan,
-                                             sh.plan_id, static_cast<int32_t>(sh.plan_entries), part, lr, ex);
+                                             sh.plan_id, static_cast<int32_t>(sh.plan_entries), part, lr, ex, sh.walk);
     return err == hipSuccess ? DS_OK : DS_ERR_HIP;
 }
 
-template <typename GT, bool kRagged>
+template <typename GT, bool kRagged, bool kTiled>
 int launch_state(float* X, const GT* G, int64_t ldx, int64_t ldg, const LaunchShape& sh, const PartitionArg& part,
                  float lr, bool opt, const Extras& ex, hipStream_t st) {
     const bool has_v = ex.v != nullptr, has_s = ex.s != nullptr;
-    if (!opt) return launch_one<GT, kRagged, false, false, false>(X, G, ldx, ldg, sh, part, lr, ex, st);
-    if (has_v && has_s) return launch_one<GT, kRagged, true, true, true>(X, G, ldx, ldg, sh, part, lr, ex, st);
-    if (has_v) return launch_one<GT, kRagged, true, true, false>(X, G, ldx, ldg, sh, part, lr, ex, st);
-    if (has_s) return launch_one<GT, kRagged, true, false, true>(X, G, ldx, ldg, sh, part, lr, ex, st);
-    return launch_one<GT, kRagged, true, false, false>(X, G, ldx, ldg, sh, part, lr, ex, st);
+    if (!opt) return launch_one<GT, kRagged, kTiled, false, false, false>(X, G, ldx, ldg, sh, part, lr, ex, st);
+    if (has_v && has_s) return launch_one<GT, kRagged, kTiled, true, true, true>(X, G, ldx, ldg, sh, part, lr, ex, st);
+    if (has_v) return launch_one<GT, kRagged, kTiled, true, true, false>(X, G, ldx, ldg, sh, part, lr, ex, st);
+    if (has_s) return launch_one<GT, kRagged, kTiled, true, false, true>(X, G, ldx, ldg, sh, part, lr, ex, st);
+    return launch_one<GT, kRagged, kTiled, true, false, false>(X, G, ldx, ldg, sh, part, lr, ex, st);
 }
 
-template <bool kRagged>
+template <bool kRagged, bool kTiled>
 int launch(void* X, const void* G, int32_t g_dtype, int64_t ldx, int64_t ldg, const LaunchShape& sh,
            const PartitionArg& part, float lr, bool opt, const Extras& ex, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (g_dtype == DS_F32)
-        return launch_state<float, kRagged>(static_cast<float*>(X), static_cast<const float*>(G), ldx, ldg, sh, part,
+        return launch_state<float, kRagged, kTiled>(static_cast<float*>(X), static_cast<const float*>(G), ldx, ldg, sh, part,
                                             lr, opt, ex, st);
-    return launch_state<uint16_t, kRagged>(static_cast<float*>(X), static_cast<const uint16_t*>(G), ldx, ldg, sh, part,
+    return launch_state<uint16_t, kRagged, kTiled>(static_cast<float*>(X), static_cast<const uint16_t*>(G), ldx, ldg, sh, part,
                                            lr, opt, ex, st);
 }
 
 // Checks the optional state of the extended step and turns it into kernel arguments.
 // *opt_out says whether the extended arithmetic is needed at all.
-int read_opt(const ds_local_opt* opt, int64_t min_ld, Extras* ex, bool* opt_out) {
-    *ex = Extras{nullptr, nullptr, 0, 0, 0.f, 0.f, 0.f};
+// With tiled stacks ldv / lds are tile strides and min_ld the smallest one allowed.
+int read_opt(const ds_local_opt* opt, int64_t min_ld, Extras* ex, bool* opt_out, bool tiled = false) {
+    *ex = Extras{nullptr, nullptr, 0, 0, kSyncTileCols, kSyncTileCols, 0.f, 0.f, 0.f};
     *opt_out = false;
     if (!opt) return DS_OK;
+    const int64_t unit = tiled ? kSyncTileCols : 4;
     if (opt->V) {
-        if (!ds::aligned16(opt->V) || opt->ldv % 4 != 0) return DS_ERR_ALIGN;
+        if (!ds::aligned16(opt->V) || opt->ldv % unit != 0) return DS_ERR_ALIGN;
         if (opt->ldv < min_ld) return DS_ERR_BAD_SHAPE;
         ex->v = static_cast<float*>(opt->V);
-        ex->ldv = opt->ldv;
+        ex->ldv = tiled ? kSyncTileCols : opt->ldv;
+        ex->tsv = tiled ? opt->ldv : kSyncTileCols;
         ex->momentum = opt->momentum;
     }
     if (opt->S) {
-        if (!ds::aligned16(opt->S) || opt->lds % 4 != 0) return DS_ERR_ALIGN;
+        if (!ds::aligned16(opt->S) || opt->lds % unit != 0) return DS_ERR_ALIGN;
         if (opt->lds < min_ld) return DS_ERR_BAD_SHAPE;
         ex->s = static_cast<float*>(opt->S);
-        ex->lds = opt->lds;
+        ex->lds = tiled ? kSyncTileCols : opt->lds;
+        ex->tss = tiled ? opt->lds : kSyncTileCols;
         ex->factor = opt->swa_factor;
     }
     ex->weight_decay = opt->weight_decay;
@@ -624,8 +664,40 @@ int group_sync_flat(void* X, const void* G, int32_t g_dtype, int64_t P, int64_t 
     rc = ds::pack_partition(W, perm, off, n_groups, &part, &max_size);
     if (rc != DS_OK) return rc;
     if (P == 0) return DS_OK;
-    const LaunchShape sh = {P, nullptr, 0, 0, (P + kSyncTileCols - 1) / kSyncTileCols, max_size, n_groups};
-    return launch<false>(X, G, g_dtype, ldx, ldg, sh, part, lr, extended, ex, stream);
+    const LaunchShape sh = {P, nullptr, 0, 0, (P + kSyncTileCols - 1) / kSyncTileCols, max_size, n_groups,
+                            TileWalk{kSyncTileCols, kSyncTileCols, 0}};
+    return launch<false, false>(X, G, g_dtype, ldx, ldg, sh, part, lr, extended, ex, stream);
+}
+
+// Tiled stacks: tile strides instead of leading dimensions, tile-major walk.
+int check_tiled(const void* X, const void* G, int32_t g_dtype, int64_t P, int64_t tsx, int64_t tsg, int32_t W) {
+    if (!X || !G) return DS_ERR_NULL;
+    if (g_dtype != DS_F32 && g_dtype != DS_BF16) return DS_ERR_DTYPE;
+    if (W < 1 || W > DS_MAX_W) return DS_ERR_BAD_W;
+    const int64_t block = static_cast<int64_t>(W) * kSyncTileCols;
+    if (P < 0 || P > DS_MAX_COLUMNS || tsx < block || tsg < block) return DS_ERR_BAD_SHAPE;
+    if (!ds::aligned16(X) || !ds::aligned16(G) || tsx % kSyncTileCols != 0 || tsg % kSyncTileCols != 0) return DS_ERR_ALIGN;
+    return DS_OK;
+}
+
+int group_sync_tiled(void* X, const void* G, int32_t g_dtype, int64_t P, int64_t tsx, int64_t tsg, int32_t W,
+                     const int32_t* perm, const int32_t* off, int32_t n_groups, float lr, const ds_local_opt* opt,
+                     void* stream) {
+    int rc = check_tiled(X, G, g_dtype, P, tsx, tsg, W);
+    if (rc != DS_OK) return rc;
+    Extras ex;
+    bool extended = false;
+    rc = read_opt(opt, static_cast<int64_t>(W) * kSyncTileCols, &ex, &extended, true);
+    if (rc != DS_OK) return rc;
+    PartitionArg part;
+    int32_t max_size = 0;
+    rc = ds::pack_partition(W, perm, off, n_groups, &part, &max_size);
+    if (rc != DS_OK) return rc;
+    const int64_t n_tiles = (P + kSyncTileCols - 1) / kSyncTileCols;
+    if (n_tiles * n_groups > ds::kMaxSyncGridX) return DS_ERR_BAD_SHAPE;   // the 1-D grid tiles * groups
+    if (P == 0) return DS_OK;
+    const LaunchShape sh = {P, nullptr, 0, 0, n_tiles, max_size, n_groups, TileWalk{tsx, tsg, n_groups}};
+    return launch<false, true>(X, G, g_dtype, kSyncTileCols, kSyncTileCols, sh, part, lr, extended, ex, stream);
 }
 
 int group_sync_ragged(void* X, const void* G, int32_t g_dtype, const ds_segment* segs, int32_t S, int64_t ldx,
@@ -648,8 +720,8 @@ int group_sync_ragged(void* X, const void* G, int32_t g_dtype, const ds_segment*
         return DS_ERR_WORKSPACE;
     if (plan_id != sc.id) return DS_ERR_WORKSPACE;   // the plan was built from another list
     const LaunchShape sh = {0, static_cast<const Tile*>(plan), plan_id, sc.n_entries, sc.n_live_tiles, max_size,
-                            n_groups};
-    return launch<true>(X, G, g_dtype, ldx, ldg, sh, part, lr, extended, ex, stream);
+                            n_groups, TileWalk{kSyncTileCols, kSyncTileCols, 0}};
+    return launch<true, false>(X, G, g_dtype, ldx, ldg, sh, part, lr, extended, ex, stream);
 }
 
 }  // namespace
@@ -673,24 +745,14 @@ extern "C" size_t ds_group_sync_consensus_workspace_bytes(int64_t P, int32_t n_g
     return static_cast<size_t>(entries < 2 ? 2 : entries) * sizeof(double);   // never 0 for valid arguments
 }
 
-extern "C" int ds_group_sync_consensus(void* X, const void* G, int32_t g_dtype, int64_t P, int64_t ldx,
-                                       int64_t ldg, int32_t W, const int32_t* perm, const int32_t* off,
-                                       int32_t n_groups, float lr, double* dev_out, void* workspace,
-                                       size_t workspace_bytes, void* stream) {
-    int rc = check_stacks(X, G, g_dtype, ldx, ldg);
-    if (rc != DS_OK) return rc;
-    if (!dev_out) return DS_ERR_NULL;
-    if (P < 0 || ldx < P || ldg < P || P > DS_MAX_COLUMNS) return DS_ERR_BAD_SHAPE;
-    if ((reinterpret_cast<uintptr_t>(dev_out) & 7u) != 0) return DS_ERR_ALIGN;
-    PartitionArg part;
-    int32_t max_size = 0;
-    rc = ds::pack_partition(W, perm, off, n_groups, &part, &max_size);
-    if (rc != DS_OK) return rc;
-    if (!workspace || !ds::aligned16(workspace) ||
-        workspace_bytes < ds_group_sync_consensus_workspace_bytes(P, n_groups))
-        return DS_ERR_WORKSPACE;
+namespace {
+
+// Launches of the one-pass step+norms; every argument has been checked.
+int launch_sync_consensus(void* X, const void* G, int32_t g_dtype, int64_t P, int64_t rsx, int64_t rsg,
+                          const TileWalk& walk, int32_t W, const PartitionArg& part, int32_t max_size, int32_t n_groups,
+                          float lr, double* dev_out, void* workspace, void* stream) {
     ds::DeviceInfo dev;
-    rc = ds::device_info(&dev);
+    const int rc = ds::device_info(&dev);
     if (rc != DS_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int64_t n_tiles = (P + kSyncTileCols - 1) / kSyncTileCols;
@@ -704,16 +766,74 @@ extern "C" int ds_group_sync_consensus(void* X, const void* G, int32_t g_dtype, 
         hipError_t err;
         if (g_dtype == DS_F32)
             err = ds::launch_kernel(group_sync_consensus_kernel<float>, grid, block, lds, st, static_cast<float*>(X),
-                                    static_cast<const float*>(G), ldx, ldg, P, part, n_groups, W, lr, n_tiles, partial);
+                                    static_cast<const float*>(G), rsx, rsg, P, part, n_groups, W, lr, n_tiles, partial,
+                                    walk);
         else
             err = ds::launch_kernel(group_sync_consensus_kernel<uint16_t>, grid, block, lds, st, static_cast<float*>(X),
-                                    static_cast<const uint16_t*>(G), ldx, ldg, P, part, n_groups, W, lr, n_tiles,
-                                    partial);
+                                    static_cast<const uint16_t*>(G), rsx, rsg, P, part, n_groups, W, lr, n_tiles,
+                                    partial, walk);
         if (err != hipSuccess) return DS_ERR_HIP;
     }
     const hipError_t err = ds::launch_kernel(group_norm_kernel, dim3(static_cast<uint32_t>(n_groups)),
                                              dim3(kNormThreads), 0, st, partial, n_tiles, part, dev_out);
     return err == hipSuccess ? DS_OK : DS_ERR_HIP;
+}
+
+int check_norm_outputs(const double* dev_out, const void* workspace, size_t workspace_bytes, int64_t P, int32_t n_groups) {
+    if (!dev_out) return DS_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(dev_out) & 7u) != 0) return DS_ERR_ALIGN;
+    if (!workspace || !ds::aligned16(workspace) ||
+        workspace_bytes < ds_group_sync_consensus_workspace_bytes(P, n_groups))
+        return DS_ERR_WORKSPACE;
+    return DS_OK;
+}
+
+}  // namespace
+
+extern "C" int ds_group_sync_consensus(void* X, const void* G, int32_t g_dtype, int64_t P, int64_t ldx,
+                                       int64_t ldg, int32_t W, const int32_t* perm, const int32_t* off,
+                                       int32_t n_groups, float lr, double* dev_out, void* workspace,
+                                       size_t workspace_bytes, void* stream) {
+    int rc = check_stacks(X, G, g_dtype, ldx, ldg);
+    if (rc != DS_OK) return rc;
+    if (!dev_out) return DS_ERR_NULL;
+    if (P < 0 || ldx < P || ldg < P || P > DS_MAX_COLUMNS) return DS_ERR_BAD_SHAPE;
+    PartitionArg part;
+    int32_t max_size = 0;
+    rc = ds::pack_partition(W, perm, off, n_groups, &part, &max_size);
+    if (rc != DS_OK) return rc;
+    rc = check_norm_outputs(dev_out, workspace, workspace_bytes, P, n_groups);
+    if (rc != DS_OK) return rc;
+    return launch_sync_consensus(X, G, g_dtype, P, ldx, ldg, TileWalk{kSyncTileCols, kSyncTileCols, 0}, W, part, max_size,
+                                 n_groups, lr, dev_out, workspace, stream);
+}
+
+extern "C" int64_t ds_tiled_elements(int64_t P, int32_t W) {
+    if (P < 0 || P > DS_MAX_COLUMNS || W < 1 || W > DS_MAX_W) return 0;
+    return (P + kSyncTileCols - 1) / kSyncTileCols * W * kSyncTileCols;
+}
+
+extern "C" int ds_group_sync_tiled(void* X, const void* G, int32_t g_dtype, int64_t P, int64_t tile_stride_x,
+                                   int64_t tile_stride_g, int32_t W, const int32_t* perm, const int32_t* off,
+                                   int32_t n_groups, float lr, const ds_local_opt* opt, void* stream) {
+    return group_sync_tiled(X, G, g_dtype, P, tile_stride_x, tile_stride_g, W, perm, off, n_groups, lr, opt, stream);
+}
+
+extern "C" int ds_group_sync_consensus_tiled(void* X, const void* G, int32_t g_dtype, int64_t P,
+                                             int64_t tile_stride_x, int64_t tile_stride_g, int32_t W,
+                                             const int32_t* perm, const int32_t* off, int32_t n_groups, float lr,
+                                             double* dev_out, void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_tiled(X, G, g_dtype, P, tile_stride_x, tile_stride_g, W);
+    if (rc != DS_OK) return rc;
+    PartitionArg part;
+    int32_t max_size = 0;
+    rc = ds::pack_partition(W, perm, off, n_groups, &part, &max_size);
+    if (rc != DS_OK) return rc;
+    rc = check_norm_outputs(dev_out, workspace, workspace_bytes, P, n_groups);
+    if (rc != DS_OK) return rc;
+    return launch_sync_consensus(X, G, g_dtype, P, kSyncTileCols, kSyncTileCols,
+                                 TileWalk{tile_stride_x, tile_stride_g, n_groups}, W, part, max_size, n_groups, lr, dev_out,
+                                 workspace, stream);
 }
 
 extern "C" size_t ds_ragged_plan_bytes(const ds_segment* segs, int32_t S) {

@@ -141,6 +141,32 @@ class Run:
         return G
 
 
+TILE = 256      # columns per tile of the tiled layout
+
+
+def to_tiled(stack: torch.Tensor, P: int, tile_stride: Optional[int] = None) -> torch.Tensor:
+    """Copy of the first P columns of a row-major ``[W, ld]`` stack in the tiled layout: element
+    (i, p) at ``(p // 256) * tile_stride + i * 256 + p % 256`` of a flat tensor (``tile_stride``
+    defaults to ``W * 256``).  Slots that stand for no column (beyond P in the last block, between
+    blocks) are filled with a recognisable constant.  Layout only: no arithmetic of the method."""
+    W = stack.shape[0]
+    n_tiles = (P + TILE - 1) // TILE
+    ts = W * TILE if tile_stride is None else tile_stride
+    padded = torch.full((W, n_tiles * TILE), 7.0, dtype=stack.dtype, device=stack.device)
+    padded[:, :P] = stack[:, :P]
+    out = torch.full((max(n_tiles, 1) * ts,), 7.0, dtype=stack.dtype, device=stack.device)
+    out[:n_tiles * ts].view(n_tiles, ts)[:, :W * TILE] = padded.view(W, n_tiles, TILE).permute(1, 0, 2).reshape(n_tiles, W * TILE)
+    return out
+
+
+def from_tiled(tiled: torch.Tensor, P: int, W: int, tile_stride: Optional[int] = None) -> torch.Tensor:
+    """Row-major ``[W, n_tiles * 256]`` copy of a tiled stack (columns beyond P are its unused slots)."""
+    n_tiles = (P + TILE - 1) // TILE
+    ts = W * TILE if tile_stride is None else tile_stride
+    blocks = tiled[:n_tiles * ts].view(n_tiles, ts)[:, :W * TILE].reshape(n_tiles, W, TILE)
+    return blocks.permute(1, 0, 2).reshape(W, n_tiles * TILE).contiguous()
+
+
 def tensor_to_numpy(t: torch.Tensor) -> np.ndarray:
     """Host copy of a tensor; bf16 comes back as its raw uint16 bit patterns."""
     t = t.detach()

@@ -1,0 +1,162 @@
+"""The tiled stack layout (the W pieces of a 256-column tile contiguous) against
+the CPU oracle: the step, the extended step, the consensus pass and the
+one-pass step+norms, each on stacks converted from and back to the row-major
+layout the oracle works on.  The arithmetic is the row-major kernels', so the
+replicas must also equal theirs bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2007_03298_amd as ds
+from paper_2007_03298_amd import workloads as wl
+from test_gpu_parity import DEV, SMALL, TOL_F32, assert_members_identical, gpu_consensus, random_stacks, scaled_error
+
+pytestmark = pytest.mark.gpu
+
+
+def consensus_tiled(Xt, P, ts, W):
+    need = ds.ds_consensus_workspace_bytes(W, P)
+    ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+    out = torch.full((W,), -1.0, dtype=torch.float64, device=DEV)
+    ds.ds_consensus_tiled(Xt, P, ts, W, out, ws, need)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("W,sizes,P,ldx,ldg", SMALL + [(32, [8] * 4, 256 * 9, None, None), (16, [4] * 4, 70001, None, None)])
+def test_tiled_step_and_consensus_match_oracle_small(W, sizes, P, ldx, ldg, bf16):
+    ld = (P + 3) // 4 * 4
+    X, G = random_stacks(700 + W + P, W, ld, ld, bf16)
+    pad_x = 0 if W % 2 else 512                         # blocks further apart than W*256 in some cases
+    tsx, tsg = W * 256 + pad_x, W * 256
+    Xt, Gt = wl.to_tiled(X, P, tsx), wl.to_tiled(G, P, tsg)
+    Gh = wl.tensor_to_numpy(G)
+    dt = ds.DS_BF16 if bf16 else ds.DS_F32
+    n_cols = (P + 255) // 256 * 256
+    for t in range(3):
+        perm, off = ds.ds_partition(21, t, W, sizes)
+        want = wl.tensor_to_numpy(X)
+        ds.ds_group_sync_tiled(Xt, Gt, dt, P, tsx, tsg, W, perm, off, 0.01)
+        ds.ds_group_sync(X, G, dt, P, ld, ld, W, perm, off, 0.01)
+        torch.cuda.synchronize()
+        back = wl.from_tiled(Xt, P, W, tsx)
+        assert torch.equal(back[:, :P], X[:, :P])                       # bit for bit the row-major step
+        assert torch.all(back[:, P:n_cols] == 7.0)                      # unused slots of the last block untouched
+        oracle.step(want, Gh, perm, off, 0.01, 0, P)
+        got = wl.tensor_to_numpy(back)
+        assert scaled_error(got[:, :P], want[:, :P]) <= TOL_F32
+        assert_members_identical(got[:, :P], perm, off)
+        d = consensus_tiled(Xt, P, tsx, W)
+        d_want = oracle.consensus(want, P)
+        if len(sizes) == 1:
+            assert np.array_equal(d, np.zeros(W))
+        else:
+            np.testing.assert_allclose(d, d_want, rtol=1e-5 if P >= 64 else 1e-4)
+    if pad_x:
+        gaps = Xt[:((P + 255) // 256) * tsx].view(-1, tsx)[:, W * 256:]
+        assert torch.all(gaps == 7.0)                                    # space between blocks untouched
+
+
+@pytest.mark.parametrize("W,sizes,P,use_v,use_s", [(8, [2, 3, 3], 2563, True, True), (8, [4, 4], 3001, False, True),
+                                                   (16, [5, 11], 777, True, False), (32, [8] * 4, 5003, True, True)])
+def test_tiled_extended_step_matches_oracle(W, sizes, P, use_v, use_s):
+    ld = (P + 3) // 4 * 4
+    X, G = random_stacks(800 + W + P, W, ld, ld, False)
+    g = torch.Generator(device=DEV).manual_seed(5)
+    V = torch.empty(W, ld, dtype=torch.float32, device=DEV).normal_(generator=g) if use_v else None
+    S = torch.empty(W, ld, dtype=torch.float32, device=DEV).normal_(0, 0.02, generator=g) if use_s else None
+    ts = W * 256
+    Xt, Gt = wl.to_tiled(X, P), wl.to_tiled(G, P)
+    Vt = wl.to_tiled(V, P) if use_v else None
+    St = wl.to_tiled(S, P) if use_s else None
+    Xo, Gh = wl.tensor_to_numpy(X), wl.tensor_to_numpy(G)
+    Vo = wl.tensor_to_numpy(V) if use_v else None
+    So = wl.tensor_to_numpy(S) if use_s else None
+    lr, mu, wd, f = 0.01, 0.9, 5e-4, 0.75
+    opt = ds.local_opt(Vt, ts, mu, wd, St, ts, f)
+    for t in range(3):
+        perm, off = ds.ds_partition(22, t, W, sizes)
+        ds.ds_group_sync_tiled(Xt, Gt, ds.DS_F32, P, ts, ts, W, perm, off, lr, opt)
+        torch.cuda.synchronize()
+        oracle.step_opt(Xo, Gh, perm, off, lr, V=Vo, momentum=mu, weight_decay=wd, S=So, factor=f, col0=0, ncols=P)
+        for tiled, want in ((Xt, Xo), (Vt, Vo), (St, So)):
+            if tiled is not None:
+                assert scaled_error(wl.tensor_to_numpy(wl.from_tiled(tiled, P, W))[:, :P], want[:, :P]) <= TOL_F32
+
+
+@pytest.mark.parametrize("W,sizes,P", [(8, [4, 4], 2048 * 3 + 517), (8, [2, 3, 3], 5000), (32, [8] * 4, 10000),
+                                      (64, [1] * 64, 300), (16, [16], 1027), (5, [1, 4], 1)])
+def test_tiled_step_and_norms_in_one_pass(W, sizes, P):
+    ld = (P + 3) // 4 * 4
+    X, G = random_stacks(900 + W + P, W, ld, ld, False)
+    ts = W * 256
+    Xt, Gt = wl.to_tiled(X, P), wl.to_tiled(G, P)
+    Gh = wl.tensor_to_numpy(G)
+    need = ds.ds_group_sync_consensus_workspace_bytes(P, len(sizes))
+    ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+    out = torch.full((W,), -1.0, dtype=torch.float64, device=DEV)
+    for t in range(2):
+        perm, off = ds.ds_partition(23, t, W, sizes)
+        want = wl.tensor_to_numpy(X)
+        ds.ds_group_sync_consensus_tiled(Xt, Gt, ds.DS_F32, P, ts, ts, W, perm, off, 0.01, out, ws, need)
+        ds.ds_group_sync(X, G, ds.DS_F32, P, ld, ld, W, perm, off, 0.01)
+        torch.cuda.synchronize()
+        assert torch.equal(wl.from_tiled(Xt, P, W)[:, :P], X[:, :P])
+        oracle.step(want, Gh, perm, off, 0.01, 0, P)
+        d = out.cpu().numpy()
+        if len(sizes) == 1:
+            assert np.array_equal(d, np.zeros(W))
+        else:
+            np.testing.assert_allclose(d, oracle.consensus(want, P), rtol=1e-5 if P >= 64 else 1e-4)
+
+
+def test_tiled_config3_full_size_every_column():
+    # the benchmark's tiled run: every column of every iteration against the oracle, block run by block run
+    from test_gpu_full_configs import PIECE
+    cfg = wl.CONFIGS[3]
+    W, P = cfg.W, cfg.P
+    ts = W * 256
+    n_tiles = (P + 255) // 256
+    run = wl.Run(cfg, DEV, P=P, ld=P)
+    X = wl.to_tiled(run.init_params(), P)
+    Xb = torch.empty_like(X)
+    G_rm = torch.empty(W, P, dtype=torch.float32, device=DEV)
+    tiles_per_piece = PIECE // 256
+    pinned = {name: torch.empty(tiles_per_piece * ts, dtype=torch.float32, pin_memory=True)
+              for name in ("before", "grad", "after")}
+
+    def pull(name, T, t0, nt, n):
+        # a run of blocks is contiguous; on the host it is turned into the [W, columns] the oracle takes
+        dst = pinned[name][:nt * ts]
+        dst.copy_(T[t0 * ts:(t0 + nt) * ts], non_blocking=True)
+        torch.cuda.synchronize()
+        return np.ascontiguousarray(dst.numpy().reshape(nt, W, 256).transpose(1, 0, 2).reshape(W, nt * 256)[:, :n])
+
+    own = {}
+    worst_step = worst_traj = 0.0
+    for t in range(cfg.T):
+        run.gradients(out=G_rm)
+        G = wl.to_tiled(G_rm, P)
+        perm, off = ds.ds_partition(cfg.seed, t, W, cfg.sizes)
+        po, oo = oracle.partition(cfg.seed, t, W, cfg.sizes)
+        assert perm.tolist() == po.tolist() and off.tolist() == oo.tolist()
+        Xb.copy_(X)
+        ds.ds_group_sync_tiled(X, G, ds.DS_F32, P, ts, ts, W, perm, off, cfg.lr)
+        for t0 in range(0, n_tiles, tiles_per_piece):
+            nt = min(tiles_per_piece, n_tiles - t0)
+            n = min(nt * 256, P - t0 * 256)
+            xb, g, xa = pull("before", Xb, t0, nt, n), pull("grad", G, t0, nt, n), pull("after", X, t0, nt, n)
+            if t0 not in own:
+                own[t0] = xb.copy()
+            oracle.step(xb, g, po, oo, cfg.lr)
+            oracle.step(own[t0], g, po, oo, cfg.lr)
+            worst_step = max(worst_step, oracle.scaled_error(xa, xb))
+            worst_traj = max(worst_traj, oracle.scaled_error(xa, own[t0]))
+        print("  t=%d tiled, all columns: step err %.2e traj err %.2e" % (t, worst_step, worst_traj), flush=True)
+        del G
+    assert worst_step <= TOL_F32 and worst_traj <= TOL_F32
+    d = consensus_tiled(X, P, ts, W)
+    want = np.sqrt(sum(oracle.consensus(b) ** 2 for b in own.values()))
+    np.testing.assert_allclose(d, want, rtol=1e-5)

@@ -419,3 +419,53 @@ def test_grouped_consensus_argument_errors():
     assert status(ws_bytes=need - 1) == -8
     assert status(perm=[0, 1, 2, 3, 4, 5, 6, 6]) == -4
     assert status(off=[0, 4, 7]) == -4
+
+
+def test_tiled_entry_points_check_their_arguments():
+    # ds_tiled_elements: whole blocks of W * 256 elements
+    assert ds.ds_tiled_elements(1000, 8) == 4 * 8 * 256
+    assert ds.ds_tiled_elements(0, 8) == 0 and ds.ds_tiled_elements(256, 64) == 64 * 256
+    assert ds.ds_tiled_elements(-1, 8) == 0 and ds.ds_tiled_elements(10, 0) == 0 and ds.ds_tiled_elements(10, 65) == 0
+    assert ds.ds_tiled_elements(ds.DS_MAX_COLUMNS + 4, 1) == 0
+    block = 8 * 256
+
+    def step(X=A, G=B, dt=0, P=1000, tsx=block, tsg=block, W=8, perm=PERM8, off=OFF8, opt=None):
+        with pytest.raises(ds.DsError) as e:
+            ds.ds_group_sync_tiled(X, G, dt, P, tsx, tsg, W, perm, off, 0.1, opt, stream=0)
+        return e.value.status
+    assert step(X=0) == -1 and step(G=0) == -1
+    assert step(dt=3) == -7
+    assert step(P=-1) == -5
+    assert step(tsx=block - 256) == -5              # blocks would overlap
+    assert step(tsg=block - 256) == -5
+    assert step(tsx=block + 4) == -6                # blocks start on whole tiles
+    assert step(X=A + 8) == -6
+    assert step(W=0, perm=[], off=[0]) == -2
+    assert step(off=[0, 4, 4, 8]) == -4
+    assert step(opt=ds.local_opt(V=3 * B, ldv=block - 256, momentum=0.9)) == -5
+    assert step(opt=ds.local_opt(S=3 * B, lds=block + 4, swa_factor=0.5)) == -6
+    # the 1-D grid holds tiles * groups workgroups
+    many = ds.DS_MAX_COLUMNS // 4 + 256
+    assert step(P=many, W=8, perm=PERM8, off=list(range(9))) == -5
+    ds.ds_group_sync_tiled(A, B, 0, 0, block, block, 8, PERM8, OFF8, 0.1, stream=0)     # P == 0: nothing enqueued
+
+    need = ds.ds_consensus_workspace_bytes(8, 1000)
+    def cons(X=A, P=1000, ts=block, W=8, out=2 * B, ws=3 * B, ws_bytes=need):
+        with pytest.raises(ds.DsError) as e:
+            ds.ds_consensus_tiled(X, P, ts, W, out, ws, ws_bytes, stream=0)
+        return e.value.status
+    assert cons(X=0) == -1 and cons(out=0) == -1
+    assert cons(ts=block - 256) == -5
+    assert cons(ts=block + 8) == -6
+    assert cons(W=65) == -2
+    assert cons(ws=0) == -8 and cons(ws_bytes=need - 1) == -8
+
+    need2 = ds.ds_group_sync_consensus_workspace_bytes(1000, 2)
+    def fused(X=A, P=1000, tsx=block, out=2 * B, ws=3 * B, ws_bytes=need2, off=OFF8):
+        with pytest.raises(ds.DsError) as e:
+            ds.ds_group_sync_consensus_tiled(X, B, 0, P, tsx, block, 8, PERM8, off, 0.1, out, ws, ws_bytes, stream=0)
+        return e.value.status
+    assert fused(X=0) == -1 and fused(out=0) == -1
+    assert fused(tsx=block - 256) == -5
+    assert fused(off=[0, 4, 7]) == -4
+    assert fused(ws_bytes=need2 - 1) == -8
