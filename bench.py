@@ -190,12 +190,20 @@ class Workload:
         self.X = run.init_params()
         self.use_v = args.local_opt in ("momentum", "both")
         self.use_s = args.local_opt in ("swa", "both")
+        self.Gs = [run.gradients() for _ in range(2)]      # gradient stacks resident in HBM, used in turn
+        self.tiled = bool(getattr(args, "tiled", False)) and not cfg.ragged
+        self.ts = W * wl.TILE                               # tile stride of the tiled variant
+        if self.tiled:
+            self.X = wl.to_tiled(self.X, self.P)
+            for j in range(len(self.Gs)):
+                self.Gs[j] = wl.to_tiled(self.Gs[j], self.P)
+            torch.cuda.empty_cache()
         self.V = torch.zeros_like(self.X) if self.use_v else None
         self.S = self.X.clone() if self.use_s else None
         self.weight_decay = 5e-4 if self.use_v else 0.0
-        self.opt = (ds.local_opt(self.V, self.ld, 0.9, self.weight_decay, self.S, self.ld, 0.9)
+        pitch = self.ts if self.tiled else self.ld
+        self.opt = (ds.local_opt(self.V, pitch, 0.9, self.weight_decay, self.S, pitch, 0.9)
                     if (self.use_v or self.use_s) else None)
-        self.Gs = [run.gradients() for _ in range(2)]      # gradient stacks resident in HBM, used in turn
         self.P_cons = self.ld if cfg.ragged else self.P    # ragged: the norm runs over the whole arena
         self.ws_bytes = ds.ds_consensus_workspace_bytes(W, self.P_cons)
         self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=dev)
@@ -224,12 +232,18 @@ class Workload:
         elif cfg.ragged:
             ds.ds_group_sync_ragged_opt(self.X, G, self.g_dtype, self.packed, self.ld, self.ld, self.W, perm, off,
                                         cfg.lr, self.opt, self.plan, self.plan_bytes, self.plan_id, st)
+        elif self.tiled:
+            ds.ds_group_sync_tiled(self.X, G, self.g_dtype, self.P, self.ts, self.ts, self.W, perm, off, cfg.lr,
+                                   self.opt, st)
         else:
             ds.ds_group_sync_opt(self.X, G, self.g_dtype, self.P, self.ld, self.ld, self.W, perm, off, cfg.lr,
                                  self.opt, st)
         if ev:
             ev[1].record(st)
-        ds.ds_consensus(self.X, self.P_cons, self.ld, self.W, self.dev_out, self.ws, self.ws_bytes, st)
+        if self.tiled:
+            ds.ds_consensus_tiled(self.X, self.P, self.ts, self.W, self.dev_out, self.ws, self.ws_bytes, st)
+        else:
+            ds.ds_consensus(self.X, self.P_cons, self.ld, self.W, self.dev_out, self.ws, self.ws_bytes, st)
         if ev:
             ev[2].record(st)
 
@@ -254,7 +268,7 @@ class Workload:
         """The step and the norms of its result in one pass (ds_group_sync_consensus): reported
         separately, never in `value`, whose consensus term stays the full second pass."""
         torch, ds, cfg = self.torch, self.ds, self.cfg
-        if cfg.ragged or self.opt is not None:
+        if cfg.ragged or self.opt is not None or self.tiled:
             return None
         n_groups = len(cfg.sizes)
         need = ds.ds_group_sync_consensus_workspace_bytes(self.P, n_groups)
@@ -293,10 +307,10 @@ class Workload:
         Another layout of the same workload: reported separately, never in `value`.
         Converts this workload's stacks, so it runs last."""
         torch, ds, cfg, wl = self.torch, self.ds, self.cfg, self.wl
-        if cfg.ragged or self.opt is not None:
+        if cfg.ragged or self.opt is not None or self.tiled:
             return None
         W, P, st = self.W, self.P, self.stream
-        ts = W * wl.TILE
+        ts = self.ts
         self.X = wl.to_tiled(self.X, P)
         for j in range(len(self.Gs)):
             self.Gs[j] = wl.to_tiled(self.Gs[j], P)
@@ -401,6 +415,10 @@ def main() -> int:
     ap.add_argument("--dense-rows", action="store_true",
                     help="leading dimension = P (rows start inside a cache line) instead of P rounded up to an "
                          "odd multiple of 256 elements (rows on 1-KiB boundaries)")
+    ap.add_argument("--tiled", action="store_true",
+                    help="configurations 1-4: the stacks stored tile by tile (the W pieces of a 256-column tile "
+                         "contiguous) and the *_tiled entry points instead of the row-major layout; a variant, "
+                         "so no recorded traffic is attached")
     ap.add_argument("--probe-copy", type=int, default=0, metavar="N",
                     help="also launch the plain copy kernel N times on a stack-sized buffer before the "
                          "timed region (yardstick for bandwidth and for profiler counter scaling)")
@@ -422,7 +440,7 @@ def main() -> int:
         return 2
     dev = "cuda:0"
     headline = args.config if args.config else 3
-    variant = args.local_opt != "none" or args.layerwise > 0 or args.dense_rows or args.graph > 0
+    variant = args.local_opt != "none" or args.layerwise > 0 or args.dense_rows or args.graph > 0 or args.tiled
     want_all = not args.config and not args.no_all_configs and not variant
     wk = Workload(headline, dev, args)
     cfg, W, P, ld = wk.cfg, wk.W, wk.P, wk.ld
@@ -455,17 +473,22 @@ def main() -> int:
 
     # reported separately, never part of `value`: the norm from one row per group, valid because the
     # step has just made the members of every group identical
-    perm, off = ds.ds_partition(cfg.seed, args.warmup + args.steps - 1, W, cfg.sizes)
-    ge = [torch.cuda.Event(enable_timing=True) for _ in range(11)]
-    dev_grouped = torch.zeros(W, dtype=torch.float64, device=dev)
-    ds.ds_consensus_grouped(wk.X, wk.P_cons, ld, W, perm, off, dev_grouped, wk.ws, wk.ws_bytes, stream)
-    ge[0].record(stream)
-    for k in range(10):
+    grouped = None
+    if not wk.tiled:
+        perm, off = ds.ds_partition(cfg.seed, args.warmup + args.steps - 1, W, cfg.sizes)
+        ge = [torch.cuda.Event(enable_timing=True) for _ in range(11)]
+        dev_grouped = torch.zeros(W, dtype=torch.float64, device=dev)
         ds.ds_consensus_grouped(wk.X, wk.P_cons, ld, W, perm, off, dev_grouped, wk.ws, wk.ws_bytes, stream)
-        ge[k + 1].record(stream)
-    torch.cuda.synchronize()
-    grouped_ms = sum(ge[k].elapsed_time(ge[k + 1]) for k in range(10)) / 10
-    grouped_gap = float((dev_grouped - wk.dev_out).abs().max() / wk.dev_out.abs().max().clamp_min(1e-300))
+        ge[0].record(stream)
+        for k in range(10):
+            ds.ds_consensus_grouped(wk.X, wk.P_cons, ld, W, perm, off, dev_grouped, wk.ws, wk.ws_bytes, stream)
+            ge[k + 1].record(stream)
+        torch.cuda.synchronize()
+        grouped_ms = sum(ge[k].elapsed_time(ge[k + 1]) for k in range(10)) / 10
+        grouped_gap = float((dev_grouped - wk.dev_out).abs().max() / wk.dev_out.abs().max().clamp_min(1e-300))
+        grouped = {"ms": round(grouped_ms, 4), "bytes_read": int(4.0 * len(cfg.sizes) * wk.P_cons),
+                   "note": "one row per group; valid right after a group-sync; not in value",
+                   "max_rel_gap_to_full": grouped_gap}
 
     graph_replay = None
     if args.graph > 0 and wk.layerwise is None:
@@ -515,9 +538,6 @@ def main() -> int:
         "consensus": dict(spread(cons_list), GBps=round(cons_gbps, 1),
                           pct_of_hbm_peak=round(100.0 * cons_gbps / HBM_PEAK_GBPS, 2),
                           max_deviation=float(d.max())),
-        "consensus_grouped": {"ms": round(grouped_ms, 4), "bytes_read": int(4.0 * len(cfg.sizes) * wk.P_cons),
-                              "note": "one row per group; valid right after a group-sync; not in value",
-                              "max_rel_gap_to_full": grouped_gap},
         "roofline": {"bound": "hbm", "kernel": "group_sync_kernel<float, flat>", "bytes_per_launch": int(sync_bytes),
                      "achieved": round(sync_gbps, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(sync_gbps / HBM_PEAK_GBPS, 4),
@@ -527,6 +547,13 @@ def main() -> int:
                    "compute_units": props.multi_processor_count, "hbm_GiB": round(props.total_memory / 2**30, 1),
                    "assumed_hbm_peak_GBps": HBM_PEAK_GBPS},
     }
+    if grouped is not None:
+        out["consensus_grouped"] = grouped
+    if wk.tiled:
+        out["config"]["layout"] = "tiled"
+        out["config"]["tile_stride"] = wk.ts
+        out["roofline"]["kernel"] = "group_sync_kernel<float, tiled>"
+        out["roofline"]["traffic"] = None
     if probe is not None:
         out["probe_copy"] = probe
     if graph_replay is not None:
@@ -546,7 +573,7 @@ def main() -> int:
         out["roofline"]["kernel"] = "group_sync_kernel<bf16, ragged>"
 
     cpu_inputs = None
-    if not args.no_cpu_baseline and not cfg.ragged and wk.opt is None and headline != 4:
+    if not args.no_cpu_baseline and not cfg.ragged and wk.opt is None and headline != 4 and not wk.tiled:
         import numpy as np
         cpu_inputs = (cfg, np.ascontiguousarray(wk.X[:, :P].cpu().numpy()),
                       np.ascontiguousarray(wk.Gs[0][:, :P].cpu().numpy()))
