@@ -84,7 +84,9 @@ __device__ __forceinline__ int table_byte(const uint32_t* words, int i) {
 // the fp64 division is a long sequence (3 % of the pass at 64 workers) and
 // multiplying is then exactly dividing; any other count is divided properly, so
 // that the mean of identical replicas is the replica itself to the last bit.
-template <int kWPad, int kVec, bool kFull, bool kGrouped, bool kPow2>
+// kExact: all kWPad row slots are rows (8, 16, 32 or 64 of them); the per-row
+// guard, which otherwise costs a select per fp64 value, is compiled out.
+template <int kWPad, int kVec, bool kFull, bool kGrouped, bool kPow2, bool kExact>
 __device__ __forceinline__ void consensus_tile(float (&acc)[kWPad], const float* __restrict__ X, int64_t c,
                                                int64_t P, int64_t ld, int64_t tile_stride, int W, const RowTable& tab,
                                                int total_weight, double inv_pow2) {
@@ -96,7 +98,7 @@ __device__ __forceinline__ void consensus_tile(float (&acc)[kWPad], const float*
     const float* base = X + (c >> 8) * tile_stride + (c & 255);
 #pragma unroll
     for (int i = 0; i < kWPad; ++i) {
-        if (i < W) {
+        if (kExact || i < W) {
             const int64_t r = kGrouped ? table_byte(tab.row, i) : i;
             if (kFull) {
                 row[i] = __builtin_nontemporal_load(reinterpret_cast<const vec_t*>(base + r * ld));
@@ -108,12 +110,15 @@ __device__ __forceinline__ void consensus_tile(float (&acc)[kWPad], const float*
             }
         }
     }
+    // every row's load is issued before the first value is used: left to itself the scheduler
+    // trades loads in flight for registers and waits for memory several times per tile
+    __builtin_amdgcn_sched_barrier(0);
     double mean[kVec];
 #pragma unroll
     for (int e = 0; e < kVec; ++e) mean[e] = 0.0;
 #pragma unroll
     for (int i = 0; i < kWPad; ++i) {
-        if (i < W) {
+        if (kExact || i < W) {
             const double w = kGrouped ? static_cast<double>(table_byte(tab.weight, i)) : 1.0;
 #pragma unroll
             for (int e = 0; e < kVec; ++e)
@@ -136,7 +141,7 @@ __device__ __forceinline__ void consensus_tile(float (&acc)[kWPad], const float*
     }
 #pragma unroll
     for (int i = 0; i < kWPad; ++i) {
-        if (i < W) {
+        if (kExact || i < W) {
 #pragma unroll
             for (int e = 0; e < kVec; ++e) {
                 const float d = (row[i][e] - hi[e]) - lo[e];
@@ -146,7 +151,7 @@ __device__ __forceinline__ void consensus_tile(float (&acc)[kWPad], const float*
     }
 }
 
-template <int kWPad, int kVec, bool kGrouped, bool kPow2>
+template <int kWPad, int kVec, bool kGrouped, bool kPow2, bool kExact>
 __global__ void __launch_bounds__(kThreads)
 consensus_partial_kernel(const float* __restrict__ X, int64_t P, int64_t ld, int64_t tile_stride, int W,
                          int tiles_per_block, double* __restrict__ partial, RowTable tab, int total_weight,
@@ -170,12 +175,12 @@ consensus_partial_kernel(const float* __restrict__ X, int64_t P, int64_t ld, int
     for (int64_t tile = tile0; tile < tile1; ++tile) {
         const int64_t c = tile * kTileCols + static_cast<int64_t>(threadIdx.x) * kVec;
         if ((tile + 1) * kTileCols <= P) {
-            consensus_tile<kWPad, kVec, true, kGrouped, kPow2>(acc, X, c, P, ld, tile_stride, W, tab, total_weight, inv_pow2);
+            consensus_tile<kWPad, kVec, true, kGrouped, kPow2, kExact>(acc, X, c, P, ld, tile_stride, W, tab, total_weight, inv_pow2);
         } else if (c < P) {
             if (c + kVec <= P)
-                consensus_tile<kWPad, kVec, true, kGrouped, kPow2>(acc, X, c, P, ld, tile_stride, W, tab, total_weight, inv_pow2);
+                consensus_tile<kWPad, kVec, true, kGrouped, kPow2, kExact>(acc, X, c, P, ld, tile_stride, W, tab, total_weight, inv_pow2);
             else
-                consensus_tile<kWPad, kVec, false, kGrouped, kPow2>(acc, X, c, P, ld, tile_stride, W, tab, total_weight, inv_pow2);
+                consensus_tile<kWPad, kVec, false, kGrouped, kPow2, kExact>(acc, X, c, P, ld, tile_stride, W, tab, total_weight, inv_pow2);
         }
         if (++since == kLaneColumns / kVec || tile + 1 == tile1) {
             // lanes -> wavefront in fp64, added to the wavefront's totals; the fp32 sums start over
@@ -254,11 +259,14 @@ int launch_consensus(const float* x, int64_t P, int64_t ld, int64_t tile_stride,
     const double inv_pow2 = (W & (W - 1)) == 0 ? 1.0 / static_cast<double>(W) : 0.0;
     const dim3 grid(static_cast<uint32_t>(n_blocks)), block(kThreads);
     hipError_t err;
+    // exact: every one of the w_pad row slots is a row, so the kernel needs no per-row guard
+    const bool exact = n_rows == w_pad;
+#define DS_PARTIAL_E(WP, V, POW2, EXACT) \
+    ds::launch_kernel(consensus_partial_kernel<WP, V, kGrouped, POW2, EXACT>, grid, block, 0, st, x, P, ld, tile_stride, \
+                      n_rows, tpb, partial, tab, W, inv_pow2)
 #define DS_PARTIAL(WP, V) \
-    err = inv_pow2 != 0.0 ? ds::launch_kernel(consensus_partial_kernel<WP, V, kGrouped, true>, grid, block, 0, st, x, P, ld, \
-                                              tile_stride, n_rows, tpb, partial, tab, W, inv_pow2) \
-                          : ds::launch_kernel(consensus_partial_kernel<WP, V, kGrouped, false>, grid, block, 0, st, x, P, ld, \
-                                              tile_stride, n_rows, tpb, partial, tab, W, inv_pow2)
+    err = inv_pow2 != 0.0 ? (exact ? DS_PARTIAL_E(WP, V, true, true) : DS_PARTIAL_E(WP, V, true, false)) \
+                          : (exact ? DS_PARTIAL_E(WP, V, false, true) : DS_PARTIAL_E(WP, V, false, false))
     switch (w_pad) {
         case 8: DS_PARTIAL(8, 4); break;
         case 16: DS_PARTIAL(16, 4); break;
@@ -266,6 +274,7 @@ int launch_consensus(const float* x, int64_t P, int64_t ld, int64_t tile_stride,
         default: DS_PARTIAL(64, 2); break;
     }
 #undef DS_PARTIAL
+#undef DS_PARTIAL_E
     if (err != hipSuccess) return DS_ERR_HIP;
     err = ds::launch_kernel(consensus_final_kernel, dim3(static_cast<uint32_t>(W)), block, 0, st, partial, n_blocks, w_pad,
                             dev_out, tab);
