@@ -156,16 +156,17 @@ struct TileWalk {
 // come first in program order (with kFull nothing is predicated, so they sit in
 // one basic block); the loads of member j + kAhead follow the arithmetic of
 // member j.  kAhead = kCount (everything first, order of use left to the
-// compiler) except for rounds of 4 members, where a window of 2 members in
-// flight measured 1.5-2 % faster (groups of 4 run 10 wavefronts per CU, and
-// the staggered issue suits that better than bursts of 8 loads); for rounds of
-// 8 every window from 2 to 8 members measured equal or slower than the
-// compiler's own order (7 loads, a wait for the first two, 9 loads).
+// compiler) except for rounds of 4 members with fp32 gradients, where a window
+// of 2 members in flight measured 1-2 % faster (groups of 4 run 10 wavefronts
+// per CU, and the staggered issue suits that better than bursts of 8 loads).
+// With bf16 gradients the same window measured 5 % slower, and for rounds of 8
+// every window from 2 to 8 members measured equal or slower than the compiler's
+// own order (7 loads, a wait for the first two, 9 loads).
 template <typename GT, int kCount, bool kFull, bool kOpt, bool kHasV>
 __device__ __forceinline__ void add_members(f32x4& sum, const float* xt, const GT* gt, int64_t ldx, int64_t ldg,
                                             const Extras& ex, const PartitionArg& part, int q, int col, bool live,
                                             float lr) {
-    constexpr int kAhead = (kCount == 4 && kFull) ? 2 : kCount;
+    constexpr int kAhead = (kCount == 4 && kFull && sizeof(GT) == 4 && !kHasV) ? 2 : kCount;
     f32x4 x[kCount], g[kCount], mv[kHasV ? kCount : 1];
 #pragma unroll
     for (int j = 0; j < kAhead; ++j) {
