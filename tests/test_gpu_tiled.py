@@ -59,11 +59,12 @@ def test_tiled_step_and_consensus_match_oracle_small(W, sizes, P, ldx, ldg, bf16
         assert torch.all(gaps == 7.0)                                    # space between blocks untouched
 
 
+@pytest.mark.parametrize("bf16", [False, True])
 @pytest.mark.parametrize("W,sizes,P,use_v,use_s", [(8, [2, 3, 3], 2563, True, True), (8, [4, 4], 3001, False, True),
                                                    (16, [5, 11], 777, True, False), (32, [8] * 4, 5003, True, True)])
-def test_tiled_extended_step_matches_oracle(W, sizes, P, use_v, use_s):
+def test_tiled_extended_step_matches_oracle(W, sizes, P, use_v, use_s, bf16):
     ld = (P + 3) // 4 * 4
-    X, G = random_stacks(800 + W + P, W, ld, ld, False)
+    X, G = random_stacks(800 + W + P, W, ld, ld, bf16)
     g = torch.Generator(device=DEV).manual_seed(5)
     V = torch.empty(W, ld, dtype=torch.float32, device=DEV).normal_(generator=g) if use_v else None
     S = torch.empty(W, ld, dtype=torch.float32, device=DEV).normal_(0, 0.02, generator=g) if use_s else None
@@ -78,7 +79,7 @@ def test_tiled_extended_step_matches_oracle(W, sizes, P, use_v, use_s):
     opt = ds.local_opt(Vt, ts, mu, wd, St, ts, f)
     for t in range(3):
         perm, off = ds.ds_partition(22, t, W, sizes)
-        ds.ds_group_sync_tiled(Xt, Gt, ds.DS_F32, P, ts, ts, W, perm, off, lr, opt)
+        ds.ds_group_sync_tiled(Xt, Gt, ds.DS_BF16 if bf16 else ds.DS_F32, P, ts, ts, W, perm, off, lr, opt)
         torch.cuda.synchronize()
         oracle.step_opt(Xo, Gh, perm, off, lr, V=Vo, momentum=mu, weight_decay=wd, S=So, factor=f, col0=0, ncols=P)
         for tiled, want in ((Xt, Xo), (Vt, Vo), (St, So)):
@@ -86,11 +87,13 @@ def test_tiled_extended_step_matches_oracle(W, sizes, P, use_v, use_s):
                 assert scaled_error(wl.tensor_to_numpy(wl.from_tiled(tiled, P, W))[:, :P], want[:, :P]) <= TOL_F32
 
 
+@pytest.mark.parametrize("bf16", [False, True])
 @pytest.mark.parametrize("W,sizes,P", [(8, [4, 4], 2048 * 3 + 517), (8, [2, 3, 3], 5000), (32, [8] * 4, 10000),
                                       (64, [1] * 64, 300), (16, [16], 1027), (5, [1, 4], 1)])
-def test_tiled_step_and_norms_in_one_pass(W, sizes, P):
+def test_tiled_step_and_norms_in_one_pass(W, sizes, P, bf16):
     ld = (P + 3) // 4 * 4
-    X, G = random_stacks(900 + W + P, W, ld, ld, False)
+    X, G = random_stacks(900 + W + P, W, ld, ld, bf16)
+    dt = ds.DS_BF16 if bf16 else ds.DS_F32
     ts = W * 256
     Xt, Gt = wl.to_tiled(X, P), wl.to_tiled(G, P)
     Gh = wl.tensor_to_numpy(G)
@@ -100,8 +103,8 @@ def test_tiled_step_and_norms_in_one_pass(W, sizes, P):
     for t in range(2):
         perm, off = ds.ds_partition(23, t, W, sizes)
         want = wl.tensor_to_numpy(X)
-        ds.ds_group_sync_consensus_tiled(Xt, Gt, ds.DS_F32, P, ts, ts, W, perm, off, 0.01, out, ws, need)
-        ds.ds_group_sync(X, G, ds.DS_F32, P, ld, ld, W, perm, off, 0.01)
+        ds.ds_group_sync_consensus_tiled(Xt, Gt, dt, P, ts, ts, W, perm, off, 0.01, out, ws, need)
+        ds.ds_group_sync(X, G, dt, P, ld, ld, W, perm, off, 0.01)
         torch.cuda.synchronize()
         assert torch.equal(wl.from_tiled(Xt, P, W)[:, :P], X[:, :P])
         oracle.step(want, Gh, perm, off, 0.01, 0, P)
