@@ -534,7 +534,14 @@ def main() -> int:
                    "seed": cfg.seed, "bytes_per_step": int(sync_bytes + cons_bytes)},
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "group_sync": dict(spread(sync_list), GBps=round(sync_gbps, 1),
-                           pct_of_hbm_peak=round(100.0 * sync_gbps / HBM_PEAK_GBPS, 2)),
+                           pct_of_hbm_peak=round(100.0 * sync_gbps / HBM_PEAK_GBPS, 2),
+                           # drift over the timed region, and the two resident gradient stacks apart
+                           ms_by_quarter=[round(statistics.fmean(sync_list[q * len(sync_list) // 4:
+                                                                           max((q + 1) * len(sync_list) // 4,
+                                                                               q * len(sync_list) // 4 + 1)]), 4)
+                                          for q in range(4)],
+                           ms_by_gradient_stack=[round(statistics.fmean(sync_list[(j - wk.first_timed_t) % 2::2]), 4) for j in range(2)]
+                           if len(sync_list) >= 2 else None),
         "consensus": dict(spread(cons_list), GBps=round(cons_gbps, 1),
                           pct_of_hbm_peak=round(100.0 * cons_gbps / HBM_PEAK_GBPS, 2),
                           max_deviation=float(d.max())),
