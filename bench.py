@@ -349,6 +349,14 @@ class Workload:
         ds.ds_consensus_tiled(self.X, P, ts, W, self.dev_out, self.ws, self.ws_bytes, st)
         torch.cuda.synchronize()
         gap = float((out2 - self.dev_out).abs().max() / self.dev_out.abs().max().clamp_min(1e-300))
+        # one row per group, valid because the last call above was a step with this division
+        ge = [torch.cuda.Event(enable_timing=True) for _ in range(11)]
+        for k in range(11):
+            ds.ds_consensus_grouped_tiled(self.X, P, ts, W, perm, off, out2, self.ws, self.ws_bytes, st)
+            ge[k].record(st)
+        torch.cuda.synchronize()
+        grouped_ms = statistics.median(ge[k].elapsed_time(ge[k + 1]) for k in range(10))
+        grouped_gap = float((out2 - self.dev_out).abs().max() / self.dev_out.abs().max().clamp_min(1e-300))
         sync = spread([e[0].elapsed_time(e[1]) for e in ev])
         cons = spread([e[1].elapsed_time(e[2]) for e in ev])
         fused = spread([fe[k].elapsed_time(fe[k + 1]) for k in range(steps)])
@@ -359,6 +367,7 @@ class Workload:
         return {"tile_stride": ts, "ms_per_step": round(wall, 4),
                 "GBps": round((self.sync_bytes + 4.0 * W * P) / (wall * 1e-3) / 1e9, 1),
                 "group_sync": sync, "consensus": cons, "fused_step_and_consensus": fused,
+                "consensus_grouped": {"ms": round(grouped_ms, 4), "max_rel_gap_to_full": grouped_gap},
                 "note": "the same workload with the stacks stored tile by tile (element (i, p) at "
                         "(p // 256) * W * 256 + i * 256 + p % 256): another layout, not in value"}
 

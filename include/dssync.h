@@ -449,6 +449,7 @@ int ds_group_sync_consensus(void* X, const void* G, int32_t g_dtype, int64_t P, 
  * ds_group_sync_tiled            as ds_group_sync_opt (opt may be NULL); in opt,
  *                                ldv / lds are the tile strides of V and S
  * ds_consensus_tiled             as ds_consensus
+ * ds_consensus_grouped_tiled     as ds_consensus_grouped
  * ds_group_sync_consensus_tiled  as ds_group_sync_consensus
  * with tile strides in place of leading dimensions.  Same arithmetic as the
  * row-major entry points: results are bit-identical element for element.
@@ -468,6 +469,10 @@ int ds_group_sync_tiled(void* X, const void* G, int32_t g_dtype, int64_t P, int6
 
 int ds_consensus_tiled(const void* X, int64_t P, int64_t tile_stride, int32_t W, double* dev_out,
                        void* workspace, size_t workspace_bytes, void* stream);
+
+int ds_consensus_grouped_tiled(const void* X, int64_t P, int64_t tile_stride, int32_t W, const int32_t* perm,
+                               const int32_t* off, int32_t n_groups, double* dev_out, void* workspace,
+                               size_t workspace_bytes, void* stream);
 
 int ds_group_sync_consensus_tiled(void* X, const void* G, int32_t g_dtype, int64_t P, int64_t tile_stride_x,
                                   int64_t tile_stride_g, int32_t W, const int32_t* perm, const int32_t* off,

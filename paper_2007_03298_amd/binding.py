@@ -26,7 +26,7 @@ EXPORTS = ("ds_status_string", "ds_partition", "ds_pattern", "ds_pattern_period"
            "ds_ragged_plan_bytes", "ds_ragged_plan", "ds_group_sync_ragged", "ds_group_sync_opt",
            "ds_group_sync_ragged_opt", "ds_consensus_workspace_bytes", "ds_consensus", "ds_consensus_static", "ds_consensus_grouped",
            "ds_group_sync_consensus_workspace_bytes", "ds_group_sync_consensus", "ds_tiled_elements",
-           "ds_group_sync_tiled", "ds_consensus_tiled", "ds_group_sync_consensus_tiled",
+           "ds_group_sync_tiled", "ds_consensus_tiled", "ds_consensus_grouped_tiled", "ds_group_sync_consensus_tiled",
            "ds_padded_ld")
 
 
@@ -100,6 +100,8 @@ def _load() -> ctypes.CDLL:
     lib.ds_group_sync_tiled.argtypes = [vp, vp, i32, i64, i64, i64, i32, i32p, i32p, i32, ctypes.c_float, optp, vp]
     lib.ds_consensus_tiled.restype = ctypes.c_int
     lib.ds_consensus_tiled.argtypes = [vp, i64, i64, i32, vp, vp, sz, vp]
+    lib.ds_consensus_grouped_tiled.restype = ctypes.c_int
+    lib.ds_consensus_grouped_tiled.argtypes = [vp, i64, i64, i32, i32p, i32p, i32, vp, vp, sz, vp]
     lib.ds_group_sync_consensus_tiled.restype = ctypes.c_int
     lib.ds_group_sync_consensus_tiled.argtypes = [vp, vp, i32, i64, i64, i64, i32, i32p, i32p, i32, ctypes.c_float,
                                                   vp, vp, sz, vp]
@@ -343,6 +345,14 @@ def ds_consensus_tiled(X, P: int, tile_stride: int, W: int, dev_out, workspace, 
                        stream=None) -> None:
     _check(_lib.ds_consensus_tiled(_addr(X), P, tile_stride, W, _addr(dev_out), _addr(workspace), workspace_bytes,
                                    _stream(stream)), "ds_consensus_tiled")
+
+
+def ds_consensus_grouped_tiled(X, P: int, tile_stride: int, W: int, perm, off, dev_out, workspace, workspace_bytes: int,
+                               stream=None) -> None:
+    perm, off = _i32(perm), _i32(off)
+    _check(_lib.ds_consensus_grouped_tiled(_addr(X), P, tile_stride, W, _i32p(perm), _i32p(off), len(off) - 1,
+                                           _addr(dev_out), _addr(workspace), workspace_bytes, _stream(stream)),
+           "ds_consensus_grouped_tiled")
 
 
 def ds_group_sync_consensus_tiled(X, G, g_dtype: int, P: int, tile_stride_x: int, tile_stride_g: int, W: int, perm,

@@ -310,8 +310,10 @@ extern "C" int ds_consensus(const void* X, int64_t P, int64_t ld, int32_t W, dou
                                    static_cast<double*>(workspace), static_cast<hipStream_t>(stream));
 }
 
-extern "C" int ds_consensus_tiled(const void* X, int64_t P, int64_t tile_stride, int32_t W, double* dev_out,
-                                  void* workspace, size_t workspace_bytes, void* stream) {
+namespace {
+
+int check_tiled_consensus_args(const void* X, int64_t P, int64_t tile_stride, int32_t W, const double* dev_out,
+                               const void* workspace, size_t workspace_bytes) {
     if (!X || !dev_out) return DS_ERR_NULL;
     if (W < 1 || W > DS_MAX_W) return DS_ERR_BAD_W;
     if (P < 0 || P > DS_MAX_COLUMNS || tile_stride < static_cast<int64_t>(W) * 256) return DS_ERR_BAD_SHAPE;
@@ -319,10 +321,46 @@ extern "C" int ds_consensus_tiled(const void* X, int64_t P, int64_t tile_stride,
         return DS_ERR_ALIGN;
     if (!workspace || !ds::aligned16(workspace) || workspace_bytes < ds_consensus_workspace_bytes(W, P))
         return DS_ERR_WORKSPACE;
+    return DS_OK;
+}
+
+// Row table of the grouped norm: one row per group (its first member), weighted by the group's size.
+int grouped_table(int32_t W, const int32_t* perm, const int32_t* off, int32_t n_groups, RowTable* tab) {
+    ds::PartitionArg packed;
+    int32_t max_size = 0;
+    const int rc = ds::pack_partition(W, perm, off, n_groups, &packed, &max_size);
+    if (rc != DS_OK) return rc;
+    *tab = RowTable{};
+    for (int32_t k = 0; k < n_groups; ++k) {
+        set_byte(tab->row, k, perm[off[k]]);                // the group's first member stands for all of them
+        set_byte(tab->weight, k, off[k + 1] - off[k]);
+        for (int32_t q = off[k]; q < off[k + 1]; ++q) set_byte(tab->src, perm[q], k);
+    }
+    return DS_OK;
+}
+
+}  // namespace
+
+extern "C" int ds_consensus_tiled(const void* X, int64_t P, int64_t tile_stride, int32_t W, double* dev_out,
+                                  void* workspace, size_t workspace_bytes, void* stream) {
+    const int rc = check_tiled_consensus_args(X, P, tile_stride, W, dev_out, workspace, workspace_bytes);
+    if (rc != DS_OK) return rc;
     RowTable tab = {};
     for (int32_t i = 0; i < W; ++i) set_byte(tab.src, i, i);
     return launch_consensus<false>(static_cast<const float*>(X), P, 256, tile_stride, W, W, tab, dev_out,
                                    static_cast<double*>(workspace), static_cast<hipStream_t>(stream));
+}
+
+extern "C" int ds_consensus_grouped_tiled(const void* X, int64_t P, int64_t tile_stride, int32_t W,
+                                          const int32_t* perm, const int32_t* off, int32_t n_groups, double* dev_out,
+                                          void* workspace, size_t workspace_bytes, void* stream) {
+    const int rc = check_tiled_consensus_args(X, P, tile_stride, W, dev_out, workspace, workspace_bytes);
+    if (rc != DS_OK) return rc;
+    RowTable tab;
+    const int prc = grouped_table(W, perm, off, n_groups, &tab);
+    if (prc != DS_OK) return prc;
+    return launch_consensus<true>(static_cast<const float*>(X), P, 256, tile_stride, W, n_groups, tab, dev_out,
+                                  static_cast<double*>(workspace), static_cast<hipStream_t>(stream));
 }
 
 namespace {
@@ -366,16 +404,9 @@ extern "C" int ds_consensus_grouped(const void* X, int64_t P, int64_t ld, int32_
                                     size_t workspace_bytes, void* stream) {
     const int rc = check_consensus_args(X, P, ld, W, dev_out, workspace, workspace_bytes);
     if (rc != DS_OK) return rc;
-    ds::PartitionArg packed;
-    int32_t max_size = 0;
-    const int prc = ds::pack_partition(W, perm, off, n_groups, &packed, &max_size);
+    RowTable tab;
+    const int prc = grouped_table(W, perm, off, n_groups, &tab);
     if (prc != DS_OK) return prc;
-    RowTable tab = {};
-    for (int32_t k = 0; k < n_groups; ++k) {
-        set_byte(tab.row, k, perm[off[k]]);                 // the group's first member stands for all of them
-        set_byte(tab.weight, k, off[k + 1] - off[k]);
-        for (int32_t q = off[k]; q < off[k + 1]; ++q) set_byte(tab.src, perm[q], k);
-    }
     return launch_consensus<true>(static_cast<const float*>(X), P, ld, 256, W, n_groups, tab, dev_out,
                                   static_cast<double*>(workspace), static_cast<hipStream_t>(stream));
 }

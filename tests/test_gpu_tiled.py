@@ -49,6 +49,13 @@ def test_tiled_step_and_consensus_match_oracle_small(W, sizes, P, ldx, ldg, bf16
         assert scaled_error(got[:, :P], want[:, :P]) <= TOL_F32
         assert_members_identical(got[:, :P], perm, off)
         d = consensus_tiled(Xt, P, tsx, W)
+        # one row per group is enough right after a step (members are identical)
+        need = ds.ds_consensus_workspace_bytes(W, P)
+        ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+        dg = torch.full((W,), -1.0, dtype=torch.float64, device=DEV)
+        ds.ds_consensus_grouped_tiled(Xt, P, tsx, W, perm, off, dg, ws, need)
+        torch.cuda.synchronize()
+        np.testing.assert_allclose(dg.cpu().numpy(), d, rtol=1e-6, atol=0)
         d_want = oracle.consensus(want, P)
         if len(sizes) == 1:
             assert np.array_equal(d, np.zeros(W))

@@ -460,6 +460,15 @@ def test_tiled_entry_points_check_their_arguments():
     assert cons(W=65) == -2
     assert cons(ws=0) == -8 and cons(ws_bytes=need - 1) == -8
 
+    def grouped(X=A, ts=block, off=OFF8, ws_bytes=need):
+        with pytest.raises(ds.DsError) as e:
+            ds.ds_consensus_grouped_tiled(X, 1000, ts, 8, PERM8, off, 2 * B, 3 * B, ws_bytes, stream=0)
+        return e.value.status
+    assert grouped(X=0) == -1
+    assert grouped(ts=block - 256) == -5 and grouped(ts=block + 8) == -6
+    assert grouped(off=[0, 4, 7]) == -4
+    assert grouped(ws_bytes=need - 1) == -8
+
     need2 = ds.ds_group_sync_consensus_workspace_bytes(1000, 2)
     def fused(X=A, P=1000, tsx=block, out=2 * B, ws=3 * B, ws_bytes=need2, off=OFF8):
         with pytest.raises(ds.DsError) as e:
