@@ -23,3 +23,17 @@ def test_host_code_is_clean_under_asan_and_ubsan(tmp_path):
     res = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=300)
     assert res.returncode == 0, res.stdout + res.stderr
     assert res.stdout.startswith("ok 20000")
+
+
+@pytest.mark.skipif(shutil.which("gcc") is None, reason="needs gcc")
+def test_oracle_is_clean_under_asan_and_ubsan(tmp_path):
+    # the checker itself: exact-size buffers, random windows, pitches, divisions, both gradient types, 1-4 threads
+    exe = str(tmp_path / "sanitize_oracle")
+    cmd = ["gcc", "-std=c99", "-O1", "-g", "-fopenmp", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+           "-static-libasan", os.path.join(ROOT, "tests", "sanitize_oracle.c"), os.path.join(ROOT, "oracle", "ds_oracle.c"),
+           "-lm", "-o", exe]
+    subprocess.run(cmd, check=True)
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1", UBSAN_OPTIONS="print_stacktrace=1")
+    res = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=300)
+    assert res.returncode == 0, res.stdout + res.stderr
+    assert res.stdout.startswith("ok 400")
