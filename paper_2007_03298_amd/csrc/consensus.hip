@@ -55,11 +55,6 @@ template <> struct VecOf<2> { typedef f32x2 type; };
 
 __host__ __device__ constexpr int padded_w(int W) { return W <= 8 ? 8 : W <= 16 ? 16 : W <= 32 ? 32 : 64; }
 
-// Workgroups the partial kernel aims for: enough consecutive tiles per
-// workgroup to amortise the end-of-block reduction, enough workgroups to keep
-// 256 CUs busy without a long tail (2048 and 8192 measured 1-4 % slower).
-constexpr int kTargetBlocks = 4096;
-
 // Which rows of the stack stand for what.  Plain consensus: every worker's own
 // row, weight 1.  Grouped consensus (rows of a group are known to be
 // identical, as they are right after a group-sync): one row per group, weight
@@ -242,14 +237,24 @@ int launch_consensus(const float* x, int64_t P, int64_t ld, int64_t tile_stride,
     const int vec = w_pad >= 32 ? 2 : 4;   // keeps the rows of one lane within 64 registers
     const int64_t tile_cols = static_cast<int64_t>(kThreads) * vec;
     const int64_t n_tiles = (P + tile_cols - 1) / tile_cols;
-    // consecutive tiles per workgroup: enough to amortise the end-of-block reduction,
-    // few enough to leave thousands of workgroups for the 256 CUs.  4096 workgroups are
-    // eight full rounds of the 512 that are resident at two per CU (the 64-row kernel);
-    // a count that leaves a partly filled last round measured 2-3 % slower.
-    int64_t per_block = (n_tiles + kTargetBlocks - 1) / kTargetBlocks;
+    // Workgroups come in rounds of two per CU, all resident at once (the 64-row kernel fits
+    // two per CU, the smaller ones more): ONE round wherever a lane accumulator can take a
+    // workgroup's whole run of tiles, else as many rounds as keep the runs that short.  Measured
+    // against 4096 workgroups for everything: +2 % at 32 x 25.6 M columns, +4 % at 16 x 11.7 M,
+    // +8 % at 8 x 1 M (fewer end-of-block reductions and partial rows), equal at 64 x 138 M.
+    // Runs longer than a lane accumulator takes (more than kMaxBlocks of them would be needed)
+    // are widened in mid-run by the kernel.
+    ds::DeviceInfo dev;
+    const int drc = ds::device_info(&dev);
+    if (drc != DS_OK) return drc;
+    const int64_t round = 2 * static_cast<int64_t>(dev.compute_units);
+    const int64_t lane_tiles = kLaneColumns / vec;
+    int64_t rounds = (n_tiles + lane_tiles * round - 1) / (lane_tiles * round);
+    if (rounds < 1) rounds = 1;
+    int64_t blocks = rounds * round;
+    if (blocks > kMaxBlocks) blocks = kMaxBlocks;
+    int64_t per_block = (n_tiles + blocks - 1) / blocks;
     if (per_block < 1) per_block = 1;
-    // runs longer than a lane accumulator takes are widened in mid-run: rather more workgroups
-    if (per_block > kLaneColumns / vec) per_block = (n_tiles + kMaxBlocks - 1) / kMaxBlocks;
     if (per_block > INT32_MAX) return DS_ERR_BAD_SHAPE;
     // at least one workgroup, so that P == 0 still writes a (zero) partial row
     const int64_t want_blocks = (n_tiles + per_block - 1) / per_block;
