@@ -187,10 +187,16 @@ class Workload:
         self.g_bytes = 2 if cfg.bf16_grads else 4
         self.g_dtype = ds.DS_BF16 if cfg.bf16_grads else ds.DS_F32
         run = wl.Run(cfg, dev, P=self.ld, ld=self.ld)
-        self.X = run.init_params()
+        # the replica stack is allocated BETWEEN the two resident gradient stacks, so that either of them is one
+        # stack away from it: at 35 GB per stack a stack two away lies in another third of the HBM more often
+        g_torch = torch.bfloat16 if cfg.bf16_grads else torch.float32
+        g_first = torch.empty(W, self.ld, dtype=g_torch, device=dev)
+        x_mid = torch.empty(W, self.ld, dtype=torch.float32, device=dev)
+        g_last = torch.empty(W, self.ld, dtype=g_torch, device=dev)
+        self.X = run.init_params(out=x_mid)                 # same draws in the same order as without `out`
         self.use_v = args.local_opt in ("momentum", "both")
         self.use_s = args.local_opt in ("swa", "both")
-        self.Gs = [run.gradients() for _ in range(2)]      # gradient stacks resident in HBM, used in turn
+        self.Gs = [run.gradients(out=g_first), run.gradients(out=g_last)]   # resident in HBM, used in turn
         self.tiled = bool(getattr(args, "tiled", False)) and not cfg.ragged
         self.ts = W * wl.TILE                               # tile stride of the tiled variant
         if self.tiled:

@@ -110,11 +110,15 @@ class Run:
         self.gen.manual_seed(cfg.seed)
         self.scale = None
 
-    def init_params(self) -> torch.Tensor:
-        """``X[W, ld]`` fp32, all rows equal to one ``N(0, 0.02^2)`` vector."""
+    def init_params(self, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """``X[W, ld]`` fp32, all rows equal to one ``N(0, 0.02^2)`` vector (written into ``out`` if given)."""
         x0 = torch.empty(self.ld, dtype=torch.float32, device=self.device)
         x0.normal_(0.0, 0.02, generator=self.gen)
-        X = x0.unsqueeze(0).repeat(self.cfg.W, 1).contiguous()
+        if out is not None:
+            X = out
+            X.copy_(x0.unsqueeze(0).expand(self.cfg.W, self.ld))
+        else:
+            X = x0.unsqueeze(0).repeat(self.cfg.W, 1).contiguous()
         if self.cfg.worker_scale:
             self.scale = torch.empty(self.cfg.W, 1, dtype=torch.float32, device=self.device)
             self.scale.uniform_(0.5, 2.0, generator=self.gen)
