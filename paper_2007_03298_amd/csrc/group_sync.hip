@@ -314,18 +314,21 @@ group_sync_kernel(float* __restrict__ X, const GT* __restrict__ G, int64_t ldx, 
     if (kRagged) {
         // a plan entry covers up to kPlanTileCols columns: kSub workgroups share it
         constexpr uint32_t kSub = kPlanTileCols / kTileCols;
-        // entry 0 says which plan this is: a buffer that holds another plan (or none) is left alone
+        // Entry 0 says which plan this is: a buffer that holds another plan (or none) is left alone.
+        // The header and this workgroup's entry are fetched together and judged afterwards (one wait
+        // for memory instead of one per check): the entry lies inside the buffer whatever it holds,
+        // because the host sized the grid and checked the buffer's size against the same list.
         const PlanHeader hd = *reinterpret_cast<const PlanHeader*>(tiles);
-        if (hd.id != plan_id || hd.n_entries != plan_entries) return;
         const Tile tl = tiles[1 + tile_id / kSub];
         const int32_t done = static_cast<int32_t>(tile_id % kSub) * kTileCols;
         // a table that does not belong to these stacks must not become a wild access
         int64_t ld_min = ldx < ldg ? ldx : ldg;
         if (kHasV && ex.ldv < ld_min) ld_min = ex.ldv;
         if (kHasS && ex.lds < ld_min) ld_min = ex.lds;
-        if (tl.start < 0 || (tl.start & 7) != 0 || tl.len < 0 || tl.len > kPlanTileCols || tl.start > ld_min - tl.len)
-            return;
-        if (done >= tl.len) return;
+        bool ok = (hd.id == plan_id) & (hd.n_entries == plan_entries);
+        ok &= (tl.start >= 0) & ((tl.start & 7) == 0) & (tl.len >= 0) & (tl.len <= kPlanTileCols);
+        ok &= (tl.start <= ld_min - tl.len) & (done < tl.len);
+        if (!ok) return;
         start = tl.start + done;
         len = tl.len - done < kTileCols ? tl.len - done : kTileCols;
     } else {
