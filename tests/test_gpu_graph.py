@@ -149,3 +149,50 @@ def test_every_launch_only_entry_point_replays_from_a_hip_graph(which):
         for name in ("X", "V", "S"):
             assert torch.equal(graph_state[name].view(torch.int32), eager_state[name].view(torch.int32)), (which, t, name)
         assert torch.equal(graph_state["norms"].view(torch.int64), eager_state["norms"].view(torch.int64)), (which, t)
+
+
+def test_no_entry_point_changes_the_free_device_memory():
+    # "allocates nothing": after the kernels are loaded, a round of calls to every GPU entry point leaves the
+    # device's free memory exactly where it was (hipMemGetInfo, which sees every allocation of the process)
+    from paper_2007_03298_amd import workloads as wl
+    W, P, lr = 16, 9001, 0.01
+    ld = ds.ds_padded_ld(P)
+    ts = W * 256
+    st, _ = _states(W, P, ld, 31, False)
+    tt, _ = _states(W, P, ld, 32, True)
+    G = torch.empty(W, ld, dtype=torch.float32, device=DEV).normal_()
+    Gt = wl.to_tiled(G, P)
+    Gb = G.to(torch.bfloat16)
+    perm, off = ds.ds_partition(9, 0, W, [3, 5, 8])
+    segs = [(0, 300), (512, 2049), (4096, 4000)]
+    plan_bytes = ds.ds_ragged_plan_bytes(segs)
+    plan = torch.empty(plan_bytes, dtype=torch.uint8, device=DEV)
+    side = torch.cuda.Stream()
+    need, need2 = st["ws"].numel(), st["ws2"].numel()
+
+    def round_of_calls():
+        plan_id = ds.ds_ragged_plan(segs, ld, ld, plan, plan_bytes)
+        opt = ds.local_opt(st["V"], ld, 0.9, 1e-3, st["S"], ld, 0.8)
+        opt_t = ds.local_opt(tt["V"], ts, 0.9, 1e-3, tt["S"], ts, 0.8)
+        ds.ds_group_sync(st["X"], G, ds.DS_F32, P, ld, ld, W, perm, off, lr)
+        ds.ds_group_sync(st["X"], Gb, ds.DS_BF16, P, ld, ld, W, perm, off, lr, stream=side)
+        side.synchronize()
+        ds.ds_group_sync_opt(st["X"], G, ds.DS_F32, P, ld, ld, W, perm, off, lr, opt)
+        ds.ds_group_sync_ragged(st["X"], G, ds.DS_F32, segs, ld, ld, W, perm, off, lr, plan, plan_bytes, plan_id)
+        ds.ds_group_sync_ragged_opt(st["X"], Gb, ds.DS_BF16, segs, ld, ld, W, perm, off, lr, opt, plan, plan_bytes, plan_id)
+        ds.ds_consensus(st["X"], P, ld, W, st["norms"], st["ws"], need)
+        ds.ds_consensus_static(st["X"], P, ld, W, st["norms"])
+        ds.ds_consensus_grouped(st["X"], P, ld, W, perm, off, st["norms"], st["ws"], need)
+        ds.ds_group_sync_consensus(st["X"], G, ds.DS_F32, P, ld, ld, W, perm, off, lr, st["norms"], st["ws2"], need2)
+        ds.ds_group_sync_tiled(tt["X"], Gt, ds.DS_F32, P, ts, ts, W, perm, off, lr, opt_t)
+        ds.ds_consensus_tiled(tt["X"], P, ts, W, tt["norms"], tt["ws"], need)
+        ds.ds_consensus_grouped_tiled(tt["X"], P, ts, W, perm, off, tt["norms"], tt["ws"], need)
+        ds.ds_group_sync_consensus_tiled(tt["X"], Gt, ds.DS_F32, P, ts, ts, W, perm, off, lr, tt["norms"], tt["ws2"], need2)
+        torch.cuda.synchronize()
+
+    round_of_calls()                                   # loads the kernels, resolves the static array's address
+    free_before, _ = torch.cuda.mem_get_info()
+    for _ in range(3):
+        round_of_calls()
+    free_after, _ = torch.cuda.mem_get_info()
+    assert free_after == free_before
