@@ -27,11 +27,14 @@
  *     recorded into a HIP graph.
  *   - The library keeps no state between calls, apart from two attributes of
  *     each device (number of compute units, LDS per compute unit), which are
- *     read once per process and device on the first launch there.
+ *     read once per process and device on the first launch there, and the
+ *     per-device address of the array ds_consensus_static works in.
  *   - One launch covers at most DS_MAX_COLUMNS columns; longer rows are
  *     DS_ERR_BAD_SHAPE (columns are independent, so the caller can split them).
  *   - Row-major stacks: element (worker i, column p) of a stack with leading
  *     dimension ld is at base + i*ld + p, ld >= P.  Replica stacks are fp32.
+ *     (A second, tiled layout with entry points of its own is described at
+ *     the end of this file.)
  */
 #ifndef DSSYNC_H
 #define DSSYNC_H
