@@ -58,6 +58,21 @@ def load_probe():
     return probe_copy
 
 
+def device_clocks():
+    """Clocks and memory bus of the current device as the HIP runtime reports them (through the probe library;
+    empty if that is not built): context for the assumed peak, which stays the published 8 TB/s."""
+    import ctypes
+    if not os.path.exists(PROBE_LIB):
+        return {}
+    lib = ctypes.CDLL(PROBE_LIB)
+    mem, sclk, bus = ctypes.c_int(0), ctypes.c_int(0), ctypes.c_int(0)
+    if not hasattr(lib, "bench_probe_device_clocks") or \
+            lib.bench_probe_device_clocks(ctypes.byref(mem), ctypes.byref(sclk), ctypes.byref(bus)) != 0:
+        return {}
+    return {"memory_clock_MHz": mem.value / 1e3 or None, "shader_clock_MHz": sclk.value / 1e3 or None,
+            "memory_bus_bits": bus.value or None}
+
+
 def git_blob_id(path: str) -> str:
     """What `git hash-object` prints for the file: identifies the kernel source a record belongs to."""
     with open(path, "rb") as fh:
@@ -567,7 +582,7 @@ def main() -> int:
                                                  "cfg%d W=%d g=%d P=%d ld=%d" % (headline, W, cfg.group, P, ld))},
         "device": {"name": props.name or getattr(props, "gcnArchName", ""), "arch": getattr(props, "gcnArchName", ""),
                    "compute_units": props.multi_processor_count, "hbm_GiB": round(props.total_memory / 2**30, 1),
-                   "assumed_hbm_peak_GBps": HBM_PEAK_GBPS},
+                   "assumed_hbm_peak_GBps": HBM_PEAK_GBPS, **device_clocks()},
     }
     if grouped is not None:
         out["consensus_grouped"] = grouped

@@ -45,3 +45,14 @@ extern "C" int bench_probe_copy(void* dst, const void* src, size_t bytes, void* 
         static_cast<f32x4*>(dst), static_cast<const f32x4*>(src), n_vec);
     return hipGetLastError() == hipSuccess ? 0 : -2;
 }
+
+// What the runtime reports of the current device's clocks and memory bus (kHz, kHz, bits);
+// an attribute the runtime does not know is returned as 0.  Returns 0, or -2 if no device is current.
+extern "C" int bench_probe_device_clocks(int* memory_khz, int* shader_khz, int* bus_bits) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return -2;
+    if (hipDeviceGetAttribute(memory_khz, hipDeviceAttributeMemoryClockRate, dev) != hipSuccess) *memory_khz = 0;
+    if (hipDeviceGetAttribute(shader_khz, hipDeviceAttributeClockRate, dev) != hipSuccess) *shader_khz = 0;
+    if (hipDeviceGetAttribute(bus_bits, hipDeviceAttributeMemoryBusWidth, dev) != hipSuccess) *bus_bits = 0;
+    return 0;
+}
